@@ -1,0 +1,211 @@
+/*
+ * mgg.h -- C ABI of the MI355X (gfx950) hot path of MGG's full-graph GNN layer
+ * (arXiv 2209.06800): neighbour aggregation over N(v) U {v} from a local and a halo
+ * embedding table, followed by the dense Update.
+ *
+ * One GPU, one node range.  The halo table stands in for the embedding slices that
+ * other GPUs own (section 4.2); the library issues no inter-GPU traffic.
+ *
+ * Conventions
+ *   - Every call returns an mgg_status_t; nothing throws or aborts.  On error no output
+ *     is written and mgg_last_error() holds a message (thread-local).
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HBM of the current
+ *     HIP device.  The caller owns every buffer it passes in; the library owns only what
+ *     an mgg_partition_t holds and frees it in mgg_partition_destroy().
+ *   - Device calls enqueue work on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and do not synchronise.  Calls that use the same partition must be
+ *     ordered on one stream: they share the partition's scratch buffer.
+ *   - Matrices are row-major with an explicit leading dimension counted in elements.
+ *   - MGG_BF16 data are raw bfloat16 bit patterns (uint16_t).
+ */
+#ifndef MGG_H
+#define MGG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MGG_OK = 0,
+    MGG_ERR_INVALID_ARG = 1,   /* NULL / out-of-range argument, misaligned or too-small buffer */
+    MGG_ERR_BAD_GRAPH = 2,     /* row_ptr not monotone from 0, or a column outside [0, N)      */
+    MGG_ERR_UNSUPPORTED = 3,   /* a share with >= 2^31 - 1 neighbours, or > 2^31 - 1 nodes     */
+    MGG_ERR_ALLOC = 4,         /* host or device allocation failed                             */
+    MGG_ERR_HIP = 5            /* a HIP runtime call failed (message carries hipGetErrorString) */
+} mgg_status_t;
+
+typedef enum { MGG_F32 = 0, MGG_BF16 = 1 } mgg_dtype_t;
+/* Weighting of N(v) U {v}.
+ * GCN_SYM: section 7, GCN equation, A-hat = adjacency with self-loops, taken as
+ *          D~^-1/2 (A+I) D~^-1/2 with d~ = (whole-graph degree) + 1.
+ * GIN_SUM: section 7, GIN equation: (1+eps) h_v + sum_{u in N(v)} h_u.            */
+typedef enum { MGG_AGG_GCN_SYM = 0, MGG_AGG_GIN_SUM = 1 } mgg_agg_t;
+typedef enum { MGG_ACT_NONE = 0, MGG_ACT_RELU = 1 } mgg_act_t;
+
+typedef struct mgg_partition mgg_partition_t;   /* opaque, library-owned */
+
+/* Knobs of the partition build.  They are the paper's tuning parameters (section 6):
+ * ps = neighbours per neighbour partition (1..64), dist = how many (local, remote)
+ * partition pairs one wavefront work item covers (1..1024).  0 selects the default
+ * (ps 32, dist 16, short_max 16).  Rows with at most short_max neighbours in total
+ * are handled several per wavefront; short_max < 0 disables that bin. */
+typedef struct {
+    int32_t ps;
+    int32_t dist;
+    int32_t short_max;
+    int32_t host_only;   /* nonzero: build on the host only, never touch the GPU (for
+                            checks of the integer structures); device calls on such a
+                            partition fail with MGG_ERR_INVALID_ARG */
+} mgg_build_opts_t;
+
+typedef struct {
+    int64_t num_nodes, lb, ub, n_own;
+    int64_t nnz_local, nnz_remote, num_halo;
+    int32_t num_parts, part_id;
+    int32_t ps, dist, short_max, on_device;
+    int64_t n_groups_local, n_groups_remote;  /* neighbour partitions of the two CSRs        */
+    int64_t n_short_rows;                     /* rows handled several per wavefront          */
+    int64_t n_items;                          /* wavefront work items (all non-short rows)   */
+    int64_t n_split_rows, n_split_items;      /* rows cut into > 1 item, and those items     */
+} mgg_partition_info_t;
+
+/* Caller-allocated HOST buffers for mgg_partition_export(); a NULL member is skipped.
+ * Sizes come from mgg_partition_info(). */
+typedef struct {
+    int32_t *local_row_ptr;   /* [n_own+1]                                                   */
+    int32_t *local_col;       /* [nnz_local]   neighbour id - lb                             */
+    int32_t *remote_row_ptr;  /* [n_own+1]                                                   */
+    int32_t *remote_col;      /* [nnz_remote]  position of the neighbour in halo_gid         */
+    int32_t *halo_gid;        /* [num_halo]    global ids, strictly increasing               */
+    int64_t *halo_peer_ptr;   /* [num_parts+1] halo_gid[ptr[q]..ptr[q+1]) is owned by part q */
+    int32_t *deg_own;         /* [n_own]       whole-graph degree (self-loops not counted)   */
+    int32_t *deg_halo;        /* [num_halo]                                                  */
+    int32_t *grp_local_row, *grp_local_start, *grp_local_end;      /* [n_groups_local]       */
+    int32_t *grp_remote_row, *grp_remote_start, *grp_remote_end;   /* [n_groups_remote]      */
+    int32_t *short_rows;      /* [n_short_rows] owned-row indices of the short bin           */
+    int32_t *item_row;        /* [n_items] owned row of each wavefront work item             */
+    int32_t *item_lbeg, *item_lend;   /* [n_items] range in local_col                        */
+    int32_t *item_rbeg, *item_rend;   /* [n_items] range in remote_col                       */
+    int32_t *item_slot;       /* [n_items] -1: the item is the whole row; else partial slot  */
+} mgg_partition_arrays_t;
+
+/* ---------------------------------------------------------------------------------------
+ * mgg_build_partition -- section 4.1 Step-2 (local and remote CSR of one GPU's rows),
+ * Step-3 (neighbour partitions of ps neighbours), section 4.2 / Fig. 4 (node-id range
+ * [lb, ub) per GPU, embedding ids rebased to zero), section 5.1 (pairs of local/remote
+ * partitions per wavefront).
+ *
+ * Host, synchronous.  row_ptr[num_nodes+1] (int64, row_ptr[0]==0), col_idx[nnz] (int32) and
+ * bounds[num_parts+1] are HOST pointers, read only, not retained.  Row v lists the nodes
+ * summed into v.  bounds==NULL selects the equal-node split bounds[p]=floor(N*p/P).
+ * A neighbour equal to its own row id is dropped (the self term is added by the
+ * aggregation mode); duplicates are kept.  Degrees are whole-graph row lengths.
+ * opts may be NULL (defaults).  Unless opts->host_only, the partition's arrays are copied
+ * to the current HIP device before the call returns.  *out receives the handle.
+ * Errors: INVALID_ARG, BAD_GRAPH, UNSUPPORTED, ALLOC, HIP.
+ * ------------------------------------------------------------------------------------- */
+mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, const int32_t *col_idx,
+                                 int32_t num_parts, int32_t part_id, const int64_t *bounds,
+                                 const mgg_build_opts_t *opts, mgg_partition_t **out);
+
+mgg_status_t mgg_partition_info(const mgg_partition_t *p, mgg_partition_info_t *out);
+mgg_status_t mgg_partition_export(const mgg_partition_t *p, mgg_partition_arrays_t *host_buffers);
+void         mgg_partition_destroy(mgg_partition_t *p);   /* NULL is allowed */
+
+/* ---------------------------------------------------------------------------------------
+ * mgg_aggregate -- section 1 "GNN" equation (Aggregate over N(v) U {v}); section 4.1
+ * (LR / LL / AC stages: remote rows, local rows, accumulation) run in ONE kernel launch
+ * plus a small fix-up launch for rows cut into several work items.
+ *
+ *   GCN_SYM: out[v] = sum_u x_u / sqrt(d~_u d~_v) + x_v / d~_v
+ *   GIN_SUM: out[v] = (1+eps) x_v + sum_u x_u              (eps is ignored for GCN_SYM)
+ *
+ * x_local [n_own x dim] holds the rows this GPU owns, x_halo [num_halo x dim] the rows of
+ * the halo list in halo_gid order (may be NULL iff num_halo == 0); both DEVICE, same dtype
+ * and leading dimension ld_x >= dim.  out [n_own x dim] is DEVICE fp32, ld_out >= dim,
+ * fully overwritten; it must not alias the inputs.  Accumulation is fp32.
+ * The first call with a larger dim than any before grows the partition's scratch buffer
+ * (a synchronising device allocation); later calls allocate nothing.
+ * Errors: INVALID_ARG (NULL, dim < 1, ld < dim, host-only partition), HIP, ALLOC.
+ * ------------------------------------------------------------------------------------- */
+mgg_status_t mgg_aggregate(const mgg_partition_t *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
+                           const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x,
+                           float *out, int64_t ld_out, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * mgg_update -- section 1 (Update = a fully-connected layer), section 7 (X W, ReLU, MLP):
+ *     out = act(a . w + bias)        on MFMA, fp32 accumulation.
+ * a [n_rows x d_in] DEVICE, a_dtype F32 or BF16.  w [d_in x d_out] DEVICE row-major,
+ * w_dtype F32 or BF16.  F32 weights need F32 input and use the fp32 MFMA; BF16 weights use
+ * the bf16 MFMA and an F32 input is rounded to bf16 (nearest even) on the way in.
+ * bias [d_out] DEVICE fp32 or NULL.  out [n_rows x d_out] DEVICE, out_dtype F32 or BF16
+ * (rounded nearest even).  out must not alias a.  d_out <= 512.
+ * Errors: INVALID_ARG, UNSUPPORTED (dtype combination, d_out too large), HIP.
+ * ------------------------------------------------------------------------------------- */
+mgg_status_t mgg_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in,
+                        mgg_dtype_t w_dtype, const void *w, const float *bias, int32_t d_out,
+                        mgg_act_t act, mgg_dtype_t out_dtype, void *out, int64_t ld_out, void *stream);
+
+/* One GNN layer: Aggregate, then n_linear (1 or 2) Updates (GCN: one; GIN's MLP: two). */
+typedef struct {
+    mgg_agg_t   mode;
+    float       eps;
+    int32_t     n_linear;      /* 1 or 2 */
+    int32_t     dims[3];       /* d_in, then the output width of each linear */
+    mgg_dtype_t w_dtype;       /* dtype of every weight matrix */
+    const void *w[2];          /* DEVICE, [dims[i] x dims[i+1]] row-major */
+    const float *bias[2];      /* DEVICE fp32 or NULL */
+    mgg_act_t   act[2];
+} mgg_layer_desc_t;
+
+/* Bytes of DEVICE workspace mgg_layer_forward needs (aggregation result and, for two
+ * linears, the hidden activations).  Returns 0 on bad arguments. */
+size_t mgg_layer_workspace_bytes(const mgg_partition_t *p, const mgg_layer_desc_t *layer);
+
+/* ---------------------------------------------------------------------------------------
+ * mgg_layer_forward -- section 1 "GNN" equation: h' = Update(Aggregate(...)), all on
+ * `stream`, no host synchronisation between the kernels.
+ * x_local / x_halo / ld_x as in mgg_aggregate with dim = layer->dims[0].  workspace is a
+ * DEVICE buffer of at least mgg_layer_workspace_bytes() bytes, 256-byte aligned.
+ * out [n_own x dims[n_linear]] DEVICE, out_dtype F32 or BF16.  With BF16 weights the hidden
+ * activations of a 2-linear MLP are kept in bf16.
+ * ------------------------------------------------------------------------------------- */
+mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t *layer,
+                               mgg_dtype_t x_dtype, const void *x_local, const void *x_halo, int64_t ld_x,
+                               void *workspace, size_t workspace_bytes,
+                               mgg_dtype_t out_dtype, void *out, int64_t ld_out, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * mgg_split_edge_balanced -- section 4.1 Step-1 / Algorithm 1: contiguous node ranges with
+ * about ceil(E / num_parts) edges each.  Host only.  bounds_out has num_parts+1 entries,
+ * bounds_out[0] = 0, bounds_out[num_parts] = num_nodes; interior point s is the first node
+ * index n >= the previous point with row_ptr[n] >= min(row_ptr[previous] + ceil(E/P), E).
+ * ------------------------------------------------------------------------------------- */
+mgg_status_t mgg_split_edge_balanced(int64_t num_nodes, const int64_t *row_ptr, int32_t num_parts,
+                                     int64_t *bounds_out);
+
+/* Run-time switches for experiments (ablations of section 7.2's kind).  Known keys:
+ *   "xcd_remap"   0/1  contiguous chunks of work items per XCD            (default 1)
+ *   "lds_halo"    0/1  stage halo rows through LDS ahead of accumulation  (default 0)
+ * Unknown key or bad value -> MGG_ERR_INVALID_ARG.  Not thread-safe against running calls. */
+mgg_status_t mgg_set_option(const char *key, int32_t value);
+mgg_status_t mgg_get_option(const char *key, int32_t *value);
+
+/* Time of the most recent kernel launches of this thread is not kept by the library; for
+ * measurement the caller brackets calls with events on its stream.  This helper does that
+ * with HIP events on `stream` around `iters` back-to-back calls of mgg_aggregate and returns
+ * the mean milliseconds per call (synchronises). */
+mgg_status_t mgg_time_aggregate(const mgg_partition_t *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
+                                const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x,
+                                float *out, int64_t ld_out, void *stream, int32_t iters, float *ms_per_call);
+
+const char *mgg_last_error(void);      /* thread-local, never NULL */
+const char *mgg_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MGG_H */

@@ -1,0 +1,306 @@
+"""Thin ctypes binding of ``libmgg.so``: same names as the C ABI in ``include/mgg.h``.
+
+Argument marshalling only -- every step of the path runs inside the library's HIP kernels.
+PyTorch appears here solely as the owner of device memory and of the stream handle.  There
+is no CPU fallback: if the library is missing the import of any entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmgg.so")
+
+OK, ERR_INVALID_ARG, ERR_BAD_GRAPH, ERR_UNSUPPORTED, ERR_ALLOC, ERR_HIP = range(6)
+F32, BF16 = 0, 1
+AGG_GCN_SYM, AGG_GIN_SUM = 0, 1
+ACT_NONE, ACT_RELU = 0, 1
+_MODE = {"gcn": AGG_GCN_SYM, "gin": AGG_GIN_SUM}
+_ACT = {"none": ACT_NONE, "relu": ACT_RELU}
+_STATUS_NAME = ["OK", "INVALID_ARG", "BAD_GRAPH", "UNSUPPORTED", "ALLOC", "HIP"]
+
+EXPORTED_SYMBOLS = [
+    "mgg_build_partition", "mgg_partition_info", "mgg_partition_export", "mgg_partition_destroy",
+    "mgg_aggregate", "mgg_update", "mgg_layer_workspace_bytes", "mgg_layer_forward",
+    "mgg_split_edge_balanced", "mgg_set_option", "mgg_get_option", "mgg_time_aggregate",
+    "mgg_last_error", "mgg_version",
+]
+
+
+class MggError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"MGG_ERR_{_STATUS_NAME[status] if 0 <= status < 6 else status}: {message}")
+        self.status = status
+
+
+class BuildOpts(C.Structure):
+    _fields_ = [("ps", C.c_int32), ("dist", C.c_int32), ("short_max", C.c_int32), ("host_only", C.c_int32)]
+
+
+class PartitionInfo(C.Structure):
+    _fields_ = [("num_nodes", C.c_int64), ("lb", C.c_int64), ("ub", C.c_int64), ("n_own", C.c_int64),
+                ("nnz_local", C.c_int64), ("nnz_remote", C.c_int64), ("num_halo", C.c_int64),
+                ("num_parts", C.c_int32), ("part_id", C.c_int32),
+                ("ps", C.c_int32), ("dist", C.c_int32), ("short_max", C.c_int32), ("on_device", C.c_int32),
+                ("n_groups_local", C.c_int64), ("n_groups_remote", C.c_int64),
+                ("n_short_rows", C.c_int64), ("n_items", C.c_int64),
+                ("n_split_rows", C.c_int64), ("n_split_items", C.c_int64)]
+
+
+_ARRAY_FIELDS = ["local_row_ptr", "local_col", "remote_row_ptr", "remote_col", "halo_gid", "halo_peer_ptr",
+                 "deg_own", "deg_halo", "grp_local_row", "grp_local_start", "grp_local_end",
+                 "grp_remote_row", "grp_remote_start", "grp_remote_end", "short_rows",
+                 "item_row", "item_lbeg", "item_lend", "item_rbeg", "item_rend", "item_slot"]
+
+
+class PartitionArrays(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name in _ARRAY_FIELDS]
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("mode", C.c_int), ("eps", C.c_float), ("n_linear", C.c_int32), ("dims", C.c_int32 * 3),
+                ("w_dtype", C.c_int), ("w", C.c_void_p * 2), ("bias", C.c_void_p * 2), ("act", C.c_int * 2)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libmgg.so (built in-tree by ``paper_2209_06800_amd.build``); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2209_06800_amd.build` "
+                              "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        L.mgg_last_error.restype = C.c_char_p
+        L.mgg_version.restype = C.c_char_p
+        L.mgg_layer_workspace_bytes.restype = C.c_size_t
+        L.mgg_partition_destroy.restype = None
+        L.mgg_partition_destroy.argtypes = [C.c_void_p]
+        L.mgg_build_partition.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                          C.c_void_p, C.POINTER(C.c_void_p)]
+        L.mgg_partition_info.argtypes = [C.c_void_p, C.POINTER(PartitionInfo)]
+        L.mgg_partition_export.argtypes = [C.c_void_p, C.POINTER(PartitionArrays)]
+        L.mgg_aggregate.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_int32,
+                                    C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
+        L.mgg_update.argtypes = [C.c_int64, C.c_int, C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p,
+                                 C.c_void_p, C.c_int32, C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
+        L.mgg_layer_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(LayerDesc)]
+        L.mgg_layer_forward.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.c_int, C.c_void_p, C.c_void_p,
+                                        C.c_int64, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_int64,
+                                        C.c_void_p]
+        L.mgg_split_edge_balanced.argtypes = [C.c_int64, C.c_void_p, C.c_int32, C.c_void_p]
+        L.mgg_set_option.argtypes = [C.c_char_p, C.c_int32]
+        L.mgg_get_option.argtypes = [C.c_char_p, C.POINTER(C.c_int32)]
+        L.mgg_time_aggregate.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p,
+                                         C.c_int32, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
+                                         C.POINTER(C.c_float)]
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != OK:
+        raise MggError(status, lib().mgg_last_error().decode())
+
+
+def mgg_version() -> str:
+    return lib().mgg_version().decode()
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+# ------------------------------------------------------------------------------- torch glue
+def _torch_dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _dev_ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError("device tensor expected")
+    return C.c_void_p(t.data_ptr())
+
+
+def _ld(t) -> int:
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError("row-major 2-D tensor with unit column stride expected")
+    return int(t.stride(0)) if t.shape[0] > 1 else max(int(t.stride(0)), int(t.shape[1]))
+
+
+def _stream(stream=None):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+# ------------------------------------------------------------------------------- partition
+class Partition:
+    """Owner of an ``mgg_partition_t*``."""
+
+    def __init__(self, handle: int):
+        self._h = C.c_void_p(handle)
+        self.info = PartitionInfo()
+        _check(lib().mgg_partition_info(self._h, C.byref(self.info)))
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("partition already destroyed")
+        return self._h
+
+    def destroy(self):
+        if self._h is not None:
+            lib().mgg_partition_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def export(self) -> dict:
+        """Copy every integer structure to numpy arrays (for bit-exact checks)."""
+        i = self.info
+        sizes = {
+            "local_row_ptr": i.n_own + 1, "local_col": i.nnz_local, "remote_row_ptr": i.n_own + 1,
+            "remote_col": i.nnz_remote, "halo_gid": i.num_halo, "halo_peer_ptr": i.num_parts + 1,
+            "deg_own": i.n_own, "deg_halo": i.num_halo,
+            "grp_local_row": i.n_groups_local, "grp_local_start": i.n_groups_local, "grp_local_end": i.n_groups_local,
+            "grp_remote_row": i.n_groups_remote, "grp_remote_start": i.n_groups_remote,
+            "grp_remote_end": i.n_groups_remote, "short_rows": i.n_short_rows,
+            "item_row": i.n_items, "item_lbeg": i.n_items, "item_lend": i.n_items, "item_rbeg": i.n_items,
+            "item_rend": i.n_items, "item_slot": i.n_items,
+        }
+        out = {k: np.zeros(max(int(n), 0), dtype=np.int64 if k == "halo_peer_ptr" else np.int32)
+               for k, n in sizes.items()}
+        arrs = PartitionArrays(**{k: out[k].ctypes.data for k in _ARRAY_FIELDS})
+        _check(lib().mgg_partition_export(self.handle, C.byref(arrs)))
+        return out
+
+
+def mgg_build_partition(row_ptr: np.ndarray, col_idx: np.ndarray, num_parts: int = 1, part_id: int = 0,
+                        bounds: Optional[Sequence[int]] = None, *, ps: int = 0, dist: int = 0,
+                        short_max: int = 0, host_only: bool = False, num_nodes: Optional[int] = None) -> Partition:
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    n = row_ptr.size - 1 if num_nodes is None else num_nodes
+    b = None if bounds is None else np.ascontiguousarray(bounds, dtype=np.int64)
+    if b is not None and b.size != num_parts + 1:
+        raise MggError(ERR_INVALID_ARG, "bounds must have num_parts + 1 entries")
+    opts = BuildOpts(ps, dist, short_max, int(host_only))
+    h = C.c_void_p()
+    _check(lib().mgg_build_partition(n, _np_ptr(row_ptr), _np_ptr(col_idx) if col_idx.size else None,
+                                     num_parts, part_id, _np_ptr(b), C.byref(opts), C.byref(h)))
+    return Partition(h.value)
+
+
+def mgg_split_edge_balanced(row_ptr: np.ndarray, num_parts: int) -> np.ndarray:
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
+    out = np.zeros(num_parts + 1, dtype=np.int64)
+    _check(lib().mgg_split_edge_balanced(row_ptr.size - 1, _np_ptr(row_ptr), num_parts, _np_ptr(out)))
+    return out
+
+
+def mgg_set_option(key: str, value: int):
+    _check(lib().mgg_set_option(key.encode(), int(value)))
+
+
+def mgg_get_option(key: str) -> int:
+    v = C.c_int32()
+    _check(lib().mgg_get_option(key.encode(), C.byref(v)))
+    return v.value
+
+
+# ------------------------------------------------------------------------------- device calls
+def mgg_aggregate(part: Partition, mode: str, x_local, x_halo=None, *, eps: float = 0.0, out=None,
+                  dim: Optional[int] = None, stream=None):
+    """out[n_own x dim] (fp32) = Aggregate over N(v) U {v}; tensors are torch CUDA tensors."""
+    import torch
+    dim = int(x_local.shape[1]) if dim is None else dim
+    if out is None:
+        out = torch.empty((int(part.info.n_own), dim), dtype=torch.float32, device=x_local.device)
+    _check(lib().mgg_aggregate(part.handle, _MODE[mode], eps, _torch_dtype_code(x_local), _dev_ptr(x_local),
+                               _dev_ptr(x_halo), dim, _ld(x_local), _dev_ptr(out), _ld(out), _stream(stream)))
+    return out
+
+
+def mgg_time_aggregate(part: Partition, mode: str, x_local, x_halo, out, *, eps: float = 0.0, iters: int = 20,
+                       dim: Optional[int] = None, stream=None) -> float:
+    """Mean milliseconds per mgg_aggregate call, HIP events on the launch stream."""
+    dim = int(x_local.shape[1]) if dim is None else dim
+    ms = C.c_float()
+    _check(lib().mgg_time_aggregate(part.handle, _MODE[mode], eps, _torch_dtype_code(x_local), _dev_ptr(x_local),
+                                    _dev_ptr(x_halo), dim, _ld(x_local), _dev_ptr(out), _ld(out), _stream(stream),
+                                    iters, C.byref(ms)))
+    return float(ms.value)
+
+
+def mgg_update(a, w, bias=None, act: str = "none", *, out=None, out_dtype=None, stream=None):
+    """out = act(a @ w + bias) on MFMA."""
+    import torch
+    n_rows, d_in = int(a.shape[0]), int(a.shape[1])
+    d_out = int(w.shape[1])
+    if int(w.shape[0]) != d_in or not w.is_contiguous():
+        raise ValueError("w must be a contiguous [d_in x d_out] matrix")
+    if out is None:
+        out = torch.empty((n_rows, d_out), dtype=out_dtype or torch.float32, device=a.device)
+    _check(lib().mgg_update(n_rows, _torch_dtype_code(a), _dev_ptr(a), _ld(a), d_in, _torch_dtype_code(w),
+                            _dev_ptr(w), _dev_ptr(bias), d_out, _ACT[act], _torch_dtype_code(out), _dev_ptr(out),
+                            _ld(out), _stream(stream)))
+    return out
+
+
+def _layer_desc(mode, eps, weights, biases, acts):
+    d = LayerDesc()
+    d.mode = _MODE[mode]
+    d.eps = eps
+    d.n_linear = len(weights)
+    d.dims[0] = int(weights[0].shape[0])
+    for i, w in enumerate(weights):
+        if not w.is_contiguous():
+            raise ValueError("weights must be contiguous")
+        d.dims[i + 1] = int(w.shape[1])
+        d.w[i] = w.data_ptr()
+        d.bias[i] = None if biases is None or biases[i] is None else biases[i].data_ptr()
+        d.act[i] = _ACT[acts[i]]
+    d.w_dtype = _torch_dtype_code(weights[0])
+    return d
+
+
+def mgg_layer_workspace_bytes(part: Partition, mode, weights, acts, eps: float = 0.0, biases=None) -> int:
+    d = _layer_desc(mode, eps, weights, biases, acts)
+    return int(lib().mgg_layer_workspace_bytes(part.handle, C.byref(d)))
+
+
+def mgg_layer_forward(part: Partition, mode: str, x_local, x_halo, weights, acts, *, eps: float = 0.0,
+                      biases=None, workspace=None, out=None, out_dtype=None, stream=None):
+    """One layer: Aggregate then 1 or 2 Updates, all enqueued on one stream."""
+    import torch
+    if len(weights) not in (1, 2):
+        raise MggError(ERR_INVALID_ARG, "a layer has 1 or 2 linears")
+    d = _layer_desc(mode, eps, weights, biases, acts)
+    need = int(lib().mgg_layer_workspace_bytes(part.handle, C.byref(d)))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x_local.device)
+    if out is None:
+        out = torch.empty((int(part.info.n_own), int(weights[-1].shape[1])), dtype=out_dtype or torch.float32,
+                          device=x_local.device)
+    _check(lib().mgg_layer_forward(part.handle, C.byref(d), _torch_dtype_code(x_local), _dev_ptr(x_local),
+                                   _dev_ptr(x_halo), _ld(x_local), _dev_ptr(workspace), workspace.numel(),
+                                   _torch_dtype_code(out), _dev_ptr(out), _ld(out), _stream(stream)))
+    return out

@@ -1,0 +1,438 @@
+// Neighbour aggregation for gfx950 (section 1 "GNN" equation; section 4.1 LR / LL / AC
+// stages; section 5.1 warp-per-partition mapping with local and remote work interleaved).
+//
+// Mapping used here, per 64-lane wavefront:
+//   - a row of the embedding table is spread over LPR lanes (LPR = 4..64, a power of two),
+//     each lane owning VEC contiguous elements per chunk (16-byte loads when the layout
+//     allows), so one load instruction fetches 64/LPR neighbour rows;
+//   - a work item is a run of neighbour partitions (<= ps neighbours each) of ONE owned row,
+//     local and remote partitions taken alternately, so every wavefront mixes both kinds;
+//   - the 64/LPR sub-wave accumulators are combined with cross-lane shuffles at the end;
+//   - short rows are handled one per sub-wave (several rows per wavefront);
+//   - rows cut into several items leave raw partial sums in scratch rows, and a second
+//     small kernel adds them in a fixed order (results do not depend on scheduling).
+// Bound by memory traffic (about 0.5 flop per byte): no MFMA here.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <type_traits>
+
+#include "mgg_internal.h"
+
+namespace mgg {
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWave * kWavesPerBlock;
+
+struct AggArgs {
+    const int32_t *local_row_ptr, *local_col, *remote_row_ptr, *remote_col;
+    const float *dinv_own, *dinv_halo;
+    const int32_t *short_rows;
+    const WorkItem *items;
+    const void *x_local, *x_halo;
+    float *out, *scratch;
+    int64_t ld_x, ld_out, scratch_ld;
+    int32_t nvec;            // vectors of VEC elements per row (dim / VEC)
+    int32_t n_items, n_item_blocks, n_short;
+    int32_t ps;
+    int32_t gcn;             // 1: symmetric normalisation, 0: plain sum
+    float self_w;            // GIN: 1 + eps
+    int32_t out_vec_ok;      // out rows allow VEC-wide stores
+};
+
+// ---- element access ---------------------------------------------------------------------
+template <bool BF16, int VEC> struct Raw;
+template <> struct Raw<false, 4> { using type = float4; };
+template <> struct Raw<false, 2> { using type = float2; };
+template <> struct Raw<false, 1> { using type = float; };
+template <> struct Raw<true, 8> { using type = uint4; };
+template <> struct Raw<true, 2> { using type = uint32_t; };
+template <> struct Raw<true, 1> { using type = uint16_t; };
+
+__device__ __forceinline__ float bf16_lo(uint32_t d) { return __uint_as_float(d << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t d) { return __uint_as_float(d & 0xffff0000u); }
+
+template <bool BF16, int VEC>
+__device__ __forceinline__ void unpack(const typename Raw<BF16, VEC>::type &r, float (&f)[VEC])
+{
+    if constexpr (!BF16) {
+        if constexpr (VEC == 4) { f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w; }
+        else if constexpr (VEC == 2) { f[0] = r.x; f[1] = r.y; }
+        else { f[0] = r; }
+    } else {
+        if constexpr (VEC == 8) {
+            f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x); f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
+            f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
+        } else if constexpr (VEC == 2) { f[0] = bf16_lo(r); f[1] = bf16_hi(r); }
+        else { f[0] = __uint_as_float(static_cast<uint32_t>(r) << 16); }
+    }
+}
+
+template <typename R> __device__ __forceinline__ R zero_raw() { R z; __builtin_memset(&z, 0, sizeof z); return z; }
+
+template <int VEC>
+__device__ __forceinline__ void store_vec(float *dst, const float (&v)[VEC], bool vec_ok)
+{
+    if (vec_ok) {
+        if constexpr (VEC == 8) {
+            reinterpret_cast<float4 *>(dst)[0] = make_float4(v[0], v[1], v[2], v[3]);
+            reinterpret_cast<float4 *>(dst)[1] = make_float4(v[4], v[5], v[6], v[7]);
+        } else if constexpr (VEC == 4) {
+            *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+        } else if constexpr (VEC == 2) {
+            *reinterpret_cast<float2 *>(dst) = make_float2(v[0], v[1]);
+        } else {
+            dst[0] = v[0];
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) dst[e] = v[e];
+    }
+}
+
+// ---- one kernel configuration --------------------------------------------------------------
+template <bool BF16_, int VEC_, int LPR_, int CH_>
+struct Cfg {
+    static constexpr bool BF16 = BF16_;
+    static constexpr int VEC = VEC_, LPR = LPR_, CH = CH_;
+    static constexpr int NPW = kWave / LPR;                 // neighbour rows per load instruction
+    static constexpr int U = (8 / CH) > 0 ? (8 / CH) : 1;   // neighbour rows in flight per lane
+    using elem = typename std::conditional<BF16, uint16_t, float>::type;
+    using raw = typename Raw<BF16, VEC>::type;
+};
+
+template <class K>
+struct Acc {
+    float v[K::CH][K::VEC];
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int c = 0; c < K::CH; ++c)
+#pragma unroll
+            for (int e = 0; e < K::VEC; ++e) v[c][e] = 0.f;
+    }
+};
+
+// Final value of an owned row from its neighbour sum: adds the self term and the row factor.
+template <class K>
+__device__ __forceinline__ void write_final(const AggArgs &a, const Acc<K> &acc, int32_t row, int lis)
+{
+    const typename K::elem *xs = static_cast<const typename K::elem *>(a.x_local) + static_cast<int64_t>(row) * a.ld_x;
+    float *o = a.out + static_cast<int64_t>(row) * a.ld_out;
+    const float dv = a.gcn ? a.dinv_own[row] : 1.f;
+    const float ws = a.gcn ? dv : a.self_w;     // GCN: dv * (sum + dv * x_v) = sum_u x_u/sqrt(du dv) + x_v/dv^2
+#pragma unroll
+    for (int c = 0; c < K::CH; ++c) {
+        const int vi = c * K::LPR + lis;
+        if (vi < a.nvec) {
+            float xv[K::VEC], r[K::VEC];
+            unpack<K::BF16, K::VEC>(*reinterpret_cast<const typename K::raw *>(xs + static_cast<int64_t>(vi) * K::VEC), xv);
+#pragma unroll
+            for (int e = 0; e < K::VEC; ++e) r[e] = dv * (acc.v[c][e] + ws * xv[e]);
+            store_vec<K::VEC>(o + static_cast<int64_t>(vi) * K::VEC, r, a.out_vec_ok);
+        }
+    }
+}
+
+template <class K>
+__device__ __forceinline__ void write_partial(const AggArgs &a, const Acc<K> &acc, int32_t slot, int lis)
+{
+    float *o = a.scratch + static_cast<int64_t>(slot) * a.scratch_ld;
+#pragma unroll
+    for (int c = 0; c < K::CH; ++c) {
+        const int vi = c * K::LPR + lis;
+        if (vi < a.nvec) store_vec<K::VEC>(o + static_cast<int64_t>(vi) * K::VEC, acc.v[c], true);
+    }
+}
+
+// Accumulate one neighbour partition: `len` (<= 64) neighbour ids are held one per lane in
+// my_idx (weights in my_w); sub-wave `sub` takes neighbours sub, sub+NPW, ...
+template <class K>
+__device__ __forceinline__ void accumulate_partition(Acc<K> &acc, const typename K::elem *table, int64_t ld,
+                                                     int my_idx, float my_w, int len, int sub, int lis, int nvec)
+{
+    const int steps = (len + K::NPW - 1) / K::NPW;
+    for (int t0 = 0; t0 < steps; t0 += K::U) {
+        typename K::raw r[K::U][K::CH];
+        float w[K::U];
+#pragma unroll
+        for (int u = 0; u < K::U; ++u) {
+            const int j = (t0 + u) * K::NPW + sub;
+            const bool ok = j < len;
+            int idx;
+            if constexpr (K::NPW == 1) {           // j is wave-uniform: scalar broadcast
+                idx = __builtin_amdgcn_readlane(my_idx, j & 63);
+                const float wj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), j & 63));
+                w[u] = ok ? wj : 0.f;
+            } else {
+                idx = __shfl(my_idx, j & 63);
+                const float wj = __shfl(my_w, j & 63);
+                w[u] = ok ? wj : 0.f;
+            }
+            const typename K::elem *rowp = table + static_cast<int64_t>(idx) * ld;
+#pragma unroll
+            for (int c = 0; c < K::CH; ++c) {
+                const int vi = c * K::LPR + lis;
+                if (ok && vi < nvec)
+                    r[u][c] = *reinterpret_cast<const typename K::raw *>(rowp + static_cast<int64_t>(vi) * K::VEC);
+                else
+                    r[u][c] = zero_raw<typename K::raw>();
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < K::U; ++u)
+#pragma unroll
+            for (int c = 0; c < K::CH; ++c) {
+                float f[K::VEC];
+                unpack<K::BF16, K::VEC>(r[u][c], f);
+#pragma unroll
+                for (int e = 0; e < K::VEC; ++e) acc.v[c][e] = fmaf(w[u], f[e], acc.v[c][e]);
+            }
+    }
+}
+
+// Load the ids (and GCN factors) of the partition starting at `pos`, one per lane.
+__device__ __forceinline__ void load_partition_ids(const int32_t *col, const float *dinv, int pos, int len, int lane,
+                                                   bool gcn, int &idx, float &w)
+{
+    idx = 0; w = 0.f;
+    if (lane < len) {
+        idx = col[pos + lane];
+        w = gcn ? dinv[idx] : 1.f;
+    }
+}
+
+// Sub-wave walk over one short neighbour list (all lanes of the sub-wave read the same id).
+template <class K>
+__device__ __forceinline__ void accumulate_list(Acc<K> &acc, const typename K::elem *table, int64_t ld,
+                                                const int32_t *col, const float *dinv, int beg, int end,
+                                                bool gcn, int lis, int nvec)
+{
+    for (int j0 = beg; j0 < end; j0 += K::U) {
+        typename K::raw r[K::U][K::CH];
+        float w[K::U];
+#pragma unroll
+        for (int u = 0; u < K::U; ++u) {
+            const bool ok = j0 + u < end;
+            const int idx = ok ? col[j0 + u] : 0;
+            w[u] = ok ? (gcn ? dinv[idx] : 1.f) : 0.f;
+            const typename K::elem *rowp = table + static_cast<int64_t>(idx) * ld;
+#pragma unroll
+            for (int c = 0; c < K::CH; ++c) {
+                const int vi = c * K::LPR + lis;
+                if (ok && vi < nvec)
+                    r[u][c] = *reinterpret_cast<const typename K::raw *>(rowp + static_cast<int64_t>(vi) * K::VEC);
+                else
+                    r[u][c] = zero_raw<typename K::raw>();
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < K::U; ++u)
+#pragma unroll
+            for (int c = 0; c < K::CH; ++c) {
+                float f[K::VEC];
+                unpack<K::BF16, K::VEC>(r[u][c], f);
+#pragma unroll
+                for (int e = 0; e < K::VEC; ++e) acc.v[c][e] = fmaf(w[u], f[e], acc.v[c][e]);
+            }
+    }
+}
+
+template <class K>
+__global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int sub = lane / K::LPR;      // which neighbour row of a load instruction
+    const int lis = lane % K::LPR;      // lane inside the sub-wave = which vector of the row
+    const typename K::elem *xl = static_cast<const typename K::elem *>(a.x_local);
+    const typename K::elem *xh = static_cast<const typename K::elem *>(a.x_halo);
+    const bool gcn = a.gcn != 0;
+    Acc<K> acc;
+    acc.clear();
+
+    if (static_cast<int>(blockIdx.x) < a.n_item_blocks) {
+        // ---- one work item per wavefront ----------------------------------------------------
+        const int item_id = __builtin_amdgcn_readfirstlane(static_cast<int>(blockIdx.x) * kWavesPerBlock + wave);
+        if (item_id >= a.n_items) return;
+        const WorkItem it = a.items[item_id];
+        const int ps = a.ps;
+        const int n_l = it.lend - it.lbeg, n_r = it.rend - it.rbeg;
+        const int g_l = (n_l + ps - 1) / ps, g_r = (n_r + ps - 1) / ps;
+        const int g_n = g_l > g_r ? g_l : g_r;
+        int idx_l, idx_r, nidx_l = 0, nidx_r = 0;
+        float w_l, w_r, nw_l = 0.f, nw_r = 0.f;
+        load_partition_ids(a.local_col, a.dinv_own, it.lbeg, min(ps, n_l), lane, gcn, idx_l, w_l);
+        load_partition_ids(a.remote_col, a.dinv_halo, it.rbeg, min(ps, n_r), lane, gcn, idx_r, w_r);
+        for (int g = 0; g < g_n; ++g) {
+            // ids of the next pair are requested before this pair's rows are gathered
+            const int off = (g + 1) * ps;
+            load_partition_ids(a.local_col, a.dinv_own, it.lbeg + off, min(ps, n_l - off), lane, gcn, nidx_l, nw_l);
+            load_partition_ids(a.remote_col, a.dinv_halo, it.rbeg + off, min(ps, n_r - off), lane, gcn, nidx_r, nw_r);
+            const int len_l = min(ps, n_l - g * ps), len_r = min(ps, n_r - g * ps);
+            if (len_l > 0) accumulate_partition<K>(acc, xl, a.ld_x, idx_l, w_l, len_l, sub, lis, a.nvec);
+            if (len_r > 0) accumulate_partition<K>(acc, xh, a.ld_x, idx_r, w_r, len_r, sub, lis, a.nvec);
+            idx_l = nidx_l; w_l = nw_l; idx_r = nidx_r; w_r = nw_r;
+        }
+        // combine the sub-wave accumulators: lanes with equal `lis` hold the same columns
+#pragma unroll
+        for (int off = K::LPR; off < kWave; off <<= 1)
+#pragma unroll
+            for (int c = 0; c < K::CH; ++c)
+#pragma unroll
+                for (int e = 0; e < K::VEC; ++e) acc.v[c][e] += __shfl_xor(acc.v[c][e], off);
+        if (sub == 0) {
+            if (it.slot < 0) write_final<K>(a, acc, it.row, lis);
+            else write_partial<K>(a, acc, it.slot, lis);
+        }
+    } else {
+        // ---- short rows: one per sub-wave -----------------------------------------------------
+        const int w_id = (static_cast<int>(blockIdx.x) - a.n_item_blocks) * kWavesPerBlock + wave;
+        const int s_id = w_id * K::NPW + sub;
+        if (s_id >= a.n_short) return;
+        const int32_t row = a.short_rows[s_id];
+        accumulate_list<K>(acc, xl, a.ld_x, a.local_col, a.dinv_own, a.local_row_ptr[row], a.local_row_ptr[row + 1],
+                           gcn, lis, a.nvec);
+        accumulate_list<K>(acc, xh, a.ld_x, a.remote_col, a.dinv_halo, a.remote_row_ptr[row], a.remote_row_ptr[row + 1],
+                           gcn, lis, a.nvec);
+        write_final<K>(a, acc, row, lis);
+    }
+}
+
+// Rows cut into several items: add the partial sums in slot order, then finish the row.
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_rows, int32_t n_split, int32_t dim,
+                                                       const float *scratch, int64_t scratch_ld, const void *x_local,
+                                                       int64_t ld_x, const float *dinv_own, int32_t gcn, float self_w,
+                                                       float *out, int64_t ld_out)
+{
+    const int64_t tid = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const int64_t total = static_cast<int64_t>(n_split) * dim;
+    if (tid >= total) return;
+    const int32_t s = static_cast<int32_t>(tid / dim), k = static_cast<int32_t>(tid % dim);
+    const SplitRow sr = split_rows[s];
+    float sum = 0.f;
+    for (int32_t i = 0; i < sr.n_slots; ++i) sum += scratch[static_cast<int64_t>(sr.first_slot + i) * scratch_ld + k];
+    float xv;
+    if constexpr (BF16)
+        xv = __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k]) << 16);
+    else
+        xv = static_cast<const float *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k];
+    const float dv = gcn ? dinv_own[sr.row] : 1.f;
+    const float ws = gcn ? dv : self_w;
+    out[static_cast<int64_t>(sr.row) * ld_out + k] = dv * (sum + ws * xv);
+}
+
+template <class K>
+hipError_t launch_cfg(const AggArgs &a, int grid, hipStream_t stream)
+{
+    hipLaunchKernelGGL(aggregate_kernel<K>, dim3(grid), dim3(kBlock), 0, stream, a);
+    return hipGetLastError();
+}
+
+// LPR = smallest power of two >= nvec (at least 4, at most 64); CH = chunks per lane.
+template <bool BF16, int VEC>
+hipError_t dispatch_shape(const AggArgs &a, int grid, hipStream_t stream, int lpr, int ch)
+{
+    if (lpr == 4) return launch_cfg<Cfg<BF16, VEC, 4, 1>>(a, grid, stream);
+    if (lpr == 8) return launch_cfg<Cfg<BF16, VEC, 8, 1>>(a, grid, stream);
+    if (lpr == 16) return launch_cfg<Cfg<BF16, VEC, 16, 1>>(a, grid, stream);
+    if (lpr == 32) return launch_cfg<Cfg<BF16, VEC, 32, 1>>(a, grid, stream);
+    if (ch == 1) return launch_cfg<Cfg<BF16, VEC, 64, 1>>(a, grid, stream);
+    if (ch == 2) return launch_cfg<Cfg<BF16, VEC, 64, 2>>(a, grid, stream);
+    if (ch <= 4) return launch_cfg<Cfg<BF16, VEC, 64, 4>>(a, grid, stream);
+    return launch_cfg<Cfg<BF16, VEC, 64, 8>>(a, grid, stream);
+}
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+}  // namespace
+
+mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
+                              const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x, float *out,
+                              int64_t ld_out, hipStream_t stream)
+{
+    const bool bf16 = x_dtype == MGG_BF16;
+    const size_t esz = bf16 ? 2 : 4;
+    const void *xh = x_halo ? x_halo : x_local;   // never dereferenced when there is no halo
+
+    // widest vector the layout allows: it must divide dim and keep every row start aligned
+    int vec = 1;
+    const int cand[3] = {bf16 ? 8 : 4, 2, 1};
+    for (int c : cand) {
+        const size_t bytes = c * esz;
+        if (dim % c == 0 && ld_x % c == 0 && aligned(x_local, bytes) && aligned(xh, bytes)) { vec = c; break; }
+    }
+    const int nvec = dim / vec;
+    // a lane holds at most 8 chunks; wider rows would need a column loop
+    if (nvec > 64 * 8) return fail(MGG_ERR_UNSUPPORTED, "dim %d too wide for %d-element vectors (max %d)", dim, vec, 64 * 8 * vec);
+    int lpr = 4;
+    while (lpr < nvec && lpr < 64) lpr <<= 1;
+    const int ch = (nvec + 63) / 64;
+
+    // scratch rows for the partial sums of split rows
+    if (p->n_split_items > 0) {
+        const int64_t need_ld = (static_cast<int64_t>(dim) + 7) / 8 * 8;
+        if (p->d.scratch_ld < need_ld) {
+            if (p->d.scratch) { MGG_HIP_TRY(hipDeviceSynchronize()); (void)hipFree(p->d.scratch); p->d.scratch = nullptr; p->d.scratch_ld = 0; }
+            const size_t bytes = static_cast<size_t>(p->n_split_items) * need_ld * sizeof(float);
+            hipError_t e = hipMalloc(reinterpret_cast<void **>(&p->d.scratch), bytes);
+            if (e != hipSuccess) return fail(MGG_ERR_ALLOC, "hipMalloc(%zu bytes of scratch): %s", bytes, hipGetErrorString(e));
+            p->d.scratch_ld = need_ld;
+        }
+    }
+
+    AggArgs a{};
+    a.local_row_ptr = p->d.local_row_ptr; a.local_col = p->d.local_col;
+    a.remote_row_ptr = p->d.remote_row_ptr; a.remote_col = p->d.remote_col;
+    a.dinv_own = p->d.dinv_own; a.dinv_halo = p->d.dinv_halo;
+    a.short_rows = p->d.short_rows; a.items = p->d.items;
+    a.x_local = x_local; a.x_halo = xh;
+    a.out = out; a.scratch = p->d.scratch;
+    a.ld_x = ld_x; a.ld_out = ld_out; a.scratch_ld = p->d.scratch_ld;
+    a.nvec = nvec;
+    a.n_items = static_cast<int32_t>(p->items.size());
+    a.n_item_blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+    a.n_short = static_cast<int32_t>(p->short_rows.size());
+    a.ps = p->ps;
+    a.gcn = mode == MGG_AGG_GCN_SYM;
+    a.self_w = 1.f + eps;
+    const size_t out_bytes = (vec >= 4 ? 4 : vec) * sizeof(float);
+    a.out_vec_ok = (ld_out % (vec >= 4 ? 4 : vec) == 0) && aligned(out, out_bytes);
+
+    const int npw = 64 / lpr;
+    const int short_waves = (a.n_short + npw - 1) / npw;
+    const int grid = a.n_item_blocks + (short_waves + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (grid > 0) {
+        hipError_t e;
+        if (bf16) {
+            if (vec == 8) e = dispatch_shape<true, 8>(a, grid, stream, lpr, ch);
+            else if (vec == 2) e = dispatch_shape<true, 2>(a, grid, stream, lpr, ch);
+            else e = dispatch_shape<true, 1>(a, grid, stream, lpr, ch);
+        } else {
+            if (vec == 4) e = dispatch_shape<false, 4>(a, grid, stream, lpr, ch);
+            else if (vec == 2) e = dispatch_shape<false, 2>(a, grid, stream, lpr, ch);
+            else e = dispatch_shape<false, 1>(a, grid, stream, lpr, ch);
+        }
+        if (e != hipSuccess) return hip_fail(e, "aggregate kernel launch");
+    }
+    const int32_t n_split = static_cast<int32_t>(p->split_rows.size());
+    if (n_split > 0) {
+        const int64_t total = static_cast<int64_t>(n_split) * dim;
+        const int fgrid = static_cast<int>((total + kBlock - 1) / kBlock);
+        if (bf16)
+            hipLaunchKernelGGL(fixup_kernel<true>, dim3(fgrid), dim3(kBlock), 0, stream, p->d.split_rows, n_split, dim,
+                               p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out);
+        else
+            hipLaunchKernelGGL(fixup_kernel<false>, dim3(fgrid), dim3(kBlock), 0, stream, p->d.split_rows, n_split, dim,
+                               p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "fix-up kernel launch");
+    }
+    return MGG_OK;
+}
+
+}  // namespace mgg

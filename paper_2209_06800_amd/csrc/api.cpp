@@ -1,0 +1,188 @@
+// Argument checking and composition of the device entry points of libmgg.
+#include <atomic>
+#include <cstring>
+
+#include "mgg_internal.h"
+
+namespace mgg {
+
+static std::atomic<int32_t> g_xcd_remap{0};
+static std::atomic<int32_t> g_lds_halo{0};
+int32_t option_xcd_remap() { return g_xcd_remap.load(); }
+int32_t option_lds_halo() { return g_lds_halo.load(); }
+
+static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline bool dtype_ok(mgg_dtype_t t) { return t == MGG_F32 || t == MGG_BF16; }
+
+static mgg_status_t check_aggregate(const mgg_partition *p, mgg_agg_t mode, mgg_dtype_t x_dtype, const void *x_local,
+                                    const void *x_halo, int32_t dim, int64_t ld_x, const float *out, int64_t ld_out)
+{
+    if (!p) return fail(MGG_ERR_INVALID_ARG, "partition is NULL");
+    if (p->device < 0) return fail(MGG_ERR_INVALID_ARG, "partition was built host-only");
+    if (mode != MGG_AGG_GCN_SYM && mode != MGG_AGG_GIN_SUM) return fail(MGG_ERR_INVALID_ARG, "unknown aggregation mode");
+    if (!dtype_ok(x_dtype)) return fail(MGG_ERR_INVALID_ARG, "unknown dtype");
+    if (dim < 1 || ld_x < dim || ld_out < dim) return fail(MGG_ERR_INVALID_ARG, "dim %d, ld_x %lld, ld_out %lld", dim, (long long)ld_x, (long long)ld_out);
+    if (p->n_own > 0 && (!x_local || !out)) return fail(MGG_ERR_INVALID_ARG, "x_local or out is NULL");
+    if (!p->halo_gid.empty() && !x_halo) return fail(MGG_ERR_INVALID_ARG, "x_halo is NULL but the partition has %zu halo rows", p->halo_gid.size());
+    const size_t esz = x_dtype == MGG_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(x_local) % esz || reinterpret_cast<uintptr_t>(x_halo) % esz || reinterpret_cast<uintptr_t>(out) % 4)
+        return fail(MGG_ERR_INVALID_ARG, "pointer not aligned to its element size");
+    int dev = -1;
+    MGG_HIP_TRY(hipGetDevice(&dev));
+    if (dev != p->device) return fail(MGG_ERR_INVALID_ARG, "partition lives on device %d, current device is %d", p->device, dev);
+    return MGG_OK;
+}
+
+static mgg_status_t check_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in,
+                                 mgg_dtype_t w_dtype, const void *w, int32_t d_out, mgg_act_t act, mgg_dtype_t out_dtype,
+                                 const void *out, int64_t ld_out)
+{
+    if (n_rows < 0 || d_in < 1 || d_out < 1 || ld_a < d_in || ld_out < d_out)
+        return fail(MGG_ERR_INVALID_ARG, "n_rows %lld, d_in %d, d_out %d, ld_a %lld, ld_out %lld", (long long)n_rows, d_in, d_out, (long long)ld_a, (long long)ld_out);
+    if (!dtype_ok(a_dtype) || !dtype_ok(w_dtype) || !dtype_ok(out_dtype)) return fail(MGG_ERR_INVALID_ARG, "unknown dtype");
+    if (act != MGG_ACT_NONE && act != MGG_ACT_RELU) return fail(MGG_ERR_INVALID_ARG, "unknown activation");
+    if (w_dtype == MGG_F32 && a_dtype != MGG_F32) return fail(MGG_ERR_UNSUPPORTED, "fp32 weights need fp32 input");
+    if (!w || (n_rows > 0 && (!a || !out))) return fail(MGG_ERR_INVALID_ARG, "NULL matrix pointer");
+    if (reinterpret_cast<uintptr_t>(a) % (a_dtype == MGG_BF16 ? 2 : 4) || reinterpret_cast<uintptr_t>(w) % (w_dtype == MGG_BF16 ? 2 : 4) ||
+        reinterpret_cast<uintptr_t>(out) % (out_dtype == MGG_BF16 ? 2 : 4))
+        return fail(MGG_ERR_INVALID_ARG, "pointer not aligned to its element size");
+    return MGG_OK;
+}
+
+struct LayerPlan {
+    int64_t ld_agg = 0, ld_hid = 0;
+    size_t agg_bytes = 0, hid_bytes = 0;
+    mgg_dtype_t hid_dtype = MGG_F32;
+};
+
+static bool plan_layer(const mgg_partition *p, const mgg_layer_desc_t *l, LayerPlan *pl)
+{
+    if (!p || !l || (l->n_linear != 1 && l->n_linear != 2)) return false;
+    for (int i = 0; i <= l->n_linear; ++i)
+        if (l->dims[i] < 1) return false;
+    pl->ld_agg = static_cast<int64_t>(round_up(static_cast<size_t>(l->dims[0]), 8));      // rows start 32-byte aligned
+    pl->agg_bytes = round_up(static_cast<size_t>(p->n_own) * pl->ld_agg * sizeof(float), 256);
+    if (l->n_linear == 2) {
+        pl->hid_dtype = l->w_dtype == MGG_BF16 ? MGG_BF16 : MGG_F32;
+        pl->ld_hid = static_cast<int64_t>(round_up(static_cast<size_t>(l->dims[1]), 8));
+        pl->hid_bytes = round_up(static_cast<size_t>(p->n_own) * pl->ld_hid * (pl->hid_dtype == MGG_BF16 ? 2 : 4), 256);
+    }
+    return true;
+}
+
+}  // namespace mgg
+
+using namespace mgg;
+
+extern "C" {
+
+mgg_status_t mgg_aggregate(const mgg_partition_t *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
+                           const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x, float *out,
+                           int64_t ld_out, void *stream)
+{
+    mgg_status_t s = check_aggregate(p, mode, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out);
+    if (s != MGG_OK) return s;
+    if (p->n_own == 0) return MGG_OK;
+    return launch_aggregate(p, mode, eps, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out, static_cast<hipStream_t>(stream));
+}
+
+mgg_status_t mgg_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in,
+                        mgg_dtype_t w_dtype, const void *w, const float *bias, int32_t d_out, mgg_act_t act,
+                        mgg_dtype_t out_dtype, void *out, int64_t ld_out, void *stream)
+{
+    mgg_status_t s = check_update(n_rows, a_dtype, a, ld_a, d_in, w_dtype, w, d_out, act, out_dtype, out, ld_out);
+    if (s != MGG_OK) return s;
+    return launch_update(n_rows, a_dtype, a, ld_a, d_in, w_dtype, w, bias, d_out, act, out_dtype, out, ld_out,
+                         static_cast<hipStream_t>(stream));
+}
+
+size_t mgg_layer_workspace_bytes(const mgg_partition_t *p, const mgg_layer_desc_t *layer)
+{
+    LayerPlan pl;
+    if (!plan_layer(p, layer, &pl)) return 0;
+    return pl.agg_bytes + pl.hid_bytes + 256;
+}
+
+mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t *layer, mgg_dtype_t x_dtype,
+                               const void *x_local, const void *x_halo, int64_t ld_x, void *workspace,
+                               size_t workspace_bytes, mgg_dtype_t out_dtype, void *out, int64_t ld_out, void *stream)
+{
+    LayerPlan pl;
+    if (!plan_layer(p, layer, &pl)) return fail(MGG_ERR_INVALID_ARG, "bad layer description");
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return fail(MGG_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    if (workspace_bytes < pl.agg_bytes + pl.hid_bytes) return fail(MGG_ERR_INVALID_ARG, "workspace too small: %zu < %zu", workspace_bytes, pl.agg_bytes + pl.hid_bytes);
+    float *agg = static_cast<float *>(workspace);
+    void *hid = static_cast<char *>(workspace) + pl.agg_bytes;
+    const int32_t d0 = layer->dims[0], d1 = layer->dims[1], d2 = layer->dims[2];
+
+    // validate everything before the first launch so that an error leaves no partial output
+    mgg_status_t s = check_aggregate(p, layer->mode, x_dtype, x_local, x_halo, d0, ld_x, agg, pl.ld_agg);
+    if (s != MGG_OK) return s;
+    if (layer->n_linear == 1)
+        s = check_update(p->n_own, MGG_F32, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], d1, layer->act[0], out_dtype, out, ld_out);
+    else {
+        s = check_update(p->n_own, MGG_F32, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], d1, layer->act[0], pl.hid_dtype, hid, pl.ld_hid);
+        if (s == MGG_OK)
+            s = check_update(p->n_own, pl.hid_dtype, hid, pl.ld_hid, d1, layer->w_dtype, layer->w[1], d2, layer->act[1], out_dtype, out, ld_out);
+    }
+    if (s != MGG_OK) return s;
+    if (p->n_own == 0) return MGG_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    s = launch_aggregate(p, layer->mode, layer->eps, x_dtype, x_local, x_halo, d0, ld_x, agg, pl.ld_agg, st);
+    if (s != MGG_OK) return s;
+    if (layer->n_linear == 1)
+        return launch_update(p->n_own, MGG_F32, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], layer->bias[0], d1,
+                             layer->act[0], out_dtype, out, ld_out, st);
+    s = launch_update(p->n_own, MGG_F32, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], layer->bias[0], d1, layer->act[0],
+                      pl.hid_dtype, hid, pl.ld_hid, st);
+    if (s != MGG_OK) return s;
+    return launch_update(p->n_own, pl.hid_dtype, hid, pl.ld_hid, d1, layer->w_dtype, layer->w[1], layer->bias[1], d2,
+                         layer->act[1], out_dtype, out, ld_out, st);
+}
+
+mgg_status_t mgg_set_option(const char *key, int32_t value)
+{
+    if (!key || (value != 0 && value != 1)) return fail(MGG_ERR_INVALID_ARG, "option value must be 0 or 1");
+    if (!std::strcmp(key, "xcd_remap")) { g_xcd_remap = value; return MGG_OK; }
+    if (!std::strcmp(key, "lds_halo")) { g_lds_halo = value; return MGG_OK; }
+    return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
+}
+
+mgg_status_t mgg_get_option(const char *key, int32_t *value)
+{
+    if (!key || !value) return fail(MGG_ERR_INVALID_ARG, "NULL argument");
+    if (!std::strcmp(key, "xcd_remap")) { *value = g_xcd_remap; return MGG_OK; }
+    if (!std::strcmp(key, "lds_halo")) { *value = g_lds_halo; return MGG_OK; }
+    return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
+}
+
+mgg_status_t mgg_time_aggregate(const mgg_partition_t *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
+                                const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x, float *out,
+                                int64_t ld_out, void *stream, int32_t iters, float *ms_per_call)
+{
+    if (iters < 1 || !ms_per_call) return fail(MGG_ERR_INVALID_ARG, "iters < 1 or ms_per_call is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // one untimed call first: it validates the arguments and grows the scratch buffer if needed
+    mgg_status_t s = mgg_aggregate(p, mode, eps, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out, stream);
+    if (s != MGG_OK) return s;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    MGG_HIP_TRY(hipEventCreate(&e0));
+    hipError_t e = hipEventCreate(&e1);
+    if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(e, "hipEventCreate"); }
+    float ms = 0.f;
+    e = hipEventRecord(e0, st);
+    for (int32_t i = 0; i < iters && e == hipSuccess && s == MGG_OK; ++i)
+        s = mgg_aggregate(p, mode, eps, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out, stream);
+    if (e == hipSuccess) e = hipEventRecord(e1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (s != MGG_OK) return s;
+    if (e != hipSuccess) return hip_fail(e, "event timing");
+    *ms_per_call = ms / static_cast<float>(iters);
+    return MGG_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+// Internal declarations shared by the translation units of libmgg (not installed).
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <vector>
+
+#include "mgg.h"
+
+namespace mgg {
+
+// One wavefront work item: a run of neighbour partitions of one owned row, from the local
+// list and from the remote list (section 5.1: a warp handles pairs of local / remote
+// partitions).  slot < 0: the item covers the whole row and writes the final value;
+// slot >= 0: it writes a raw partial sum into scratch row `slot`.
+struct WorkItem {
+    int32_t row;
+    int32_t lbeg, lend;   // range in local_col
+    int32_t rbeg, rend;   // range in remote_col
+    int32_t slot;
+    int32_t pad0, pad1;
+};
+static_assert(sizeof(WorkItem) == 32, "WorkItem is read as two 16-byte words");
+
+// A row that was cut into several items: its partial sums sit in scratch rows
+// [first_slot, first_slot + n_slots) and are combined in that order.
+struct SplitRow {
+    int32_t row;
+    int32_t first_slot;
+    int32_t n_slots;
+    int32_t pad;
+};
+
+struct DeviceArrays {
+    int32_t *local_row_ptr = nullptr, *local_col = nullptr;
+    int32_t *remote_row_ptr = nullptr, *remote_col = nullptr;
+    float *dinv_own = nullptr, *dinv_halo = nullptr;
+    int32_t *short_rows = nullptr;
+    WorkItem *items = nullptr;
+    SplitRow *split_rows = nullptr;
+    float *scratch = nullptr;          // [n_split_items x scratch_ld] partial sums
+    int64_t scratch_ld = 0;
+};
+
+}  // namespace mgg
+
+struct mgg_partition {
+    int64_t num_nodes = 0, lb = 0, ub = 0, n_own = 0;
+    int32_t num_parts = 1, part_id = 0;
+    int32_t ps = 32, dist = 16, short_max = 16;
+    int device = -1;  // HIP device the arrays live on; -1 = host only
+    std::vector<int32_t> local_row_ptr, local_col, remote_row_ptr, remote_col;
+    std::vector<int32_t> halo_gid, deg_own, deg_halo;
+    std::vector<int64_t> halo_peer_ptr;
+    std::vector<float> dinv_own, dinv_halo;
+    std::vector<int32_t> short_rows;
+    std::vector<mgg::WorkItem> items;
+    std::vector<mgg::SplitRow> split_rows;
+    int64_t n_split_items = 0;
+    int64_t n_groups_local = 0, n_groups_remote = 0;
+    mutable mgg::DeviceArrays d;  // scratch grows lazily inside const calls
+};
+
+namespace mgg {
+
+mgg_status_t fail(mgg_status_t code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+mgg_status_t hip_fail(hipError_t e, const char *what);
+
+#define MGG_HIP_TRY(expr)                                    \
+    do {                                                     \
+        hipError_t _e = (expr);                              \
+        if (_e != hipSuccess) return ::mgg::hip_fail(_e, #expr); \
+    } while (0)
+
+int32_t option_xcd_remap();
+int32_t option_lds_halo();
+
+// kernels (aggregate.hip / update.hip)
+mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
+                              const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x,
+                              float *out, int64_t ld_out, hipStream_t stream);
+mgg_status_t launch_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in,
+                           mgg_dtype_t w_dtype, const void *w, const float *bias, int32_t d_out,
+                           mgg_act_t act, mgg_dtype_t out_dtype, void *out, int64_t ld_out,
+                           hipStream_t stream);
+
+}  // namespace mgg

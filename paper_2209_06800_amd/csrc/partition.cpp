@@ -1,0 +1,342 @@
+// Host side of libmgg: partition build (section 4.1 Steps 1-3, section 4.2), export of the
+// integer structures, upload to HBM.  All integer work; the only floating-point values made
+// here are the per-node factors 1/sqrt(deg+1) of the GCN normalisation.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "mgg_internal.h"
+
+namespace mgg {
+
+static thread_local char g_err[512] = "";
+
+mgg_status_t fail(mgg_status_t code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+mgg_status_t hip_fail(hipError_t e, const char *what)
+{
+    return fail(MGG_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+const char *last_error() { return g_err; }
+
+template <typename T>
+static mgg_status_t upload(const std::vector<T> &h, T **d)
+{
+    *d = nullptr;
+    // one element at least, so that kernels never receive a null table pointer
+    size_t bytes = std::max<size_t>(h.size(), 1) * sizeof(T);
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(d), bytes);
+    if (e != hipSuccess) return fail(MGG_ERR_ALLOC, "hipMalloc(%zu bytes): %s", bytes, hipGetErrorString(e));
+    if (!h.empty()) MGG_HIP_TRY(hipMemcpy(*d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice));
+    return MGG_OK;
+}
+
+static void free_device(mgg_partition *p)
+{
+    if (p->device < 0) return;
+    DeviceArrays &d = p->d;
+    void *ptrs[] = {d.local_row_ptr, d.local_col, d.remote_row_ptr, d.remote_col, d.dinv_own,
+                    d.dinv_halo,     d.short_rows, d.items,         d.split_rows, d.scratch};
+    for (void *q : ptrs)
+        if (q) (void)hipFree(q);
+    d = DeviceArrays{};
+}
+
+static mgg_status_t upload_all(mgg_partition *p)
+{
+    int dev = 0;
+    MGG_HIP_TRY(hipGetDevice(&dev));
+    p->device = dev;
+    mgg_status_t s;
+    if ((s = upload(p->local_row_ptr, &p->d.local_row_ptr)) != MGG_OK) return s;
+    if ((s = upload(p->local_col, &p->d.local_col)) != MGG_OK) return s;
+    if ((s = upload(p->remote_row_ptr, &p->d.remote_row_ptr)) != MGG_OK) return s;
+    if ((s = upload(p->remote_col, &p->d.remote_col)) != MGG_OK) return s;
+    if ((s = upload(p->dinv_own, &p->d.dinv_own)) != MGG_OK) return s;
+    if ((s = upload(p->dinv_halo, &p->d.dinv_halo)) != MGG_OK) return s;
+    if ((s = upload(p->short_rows, &p->d.short_rows)) != MGG_OK) return s;
+    if ((s = upload(p->items, &p->d.items)) != MGG_OK) return s;
+    if ((s = upload(p->split_rows, &p->d.split_rows)) != MGG_OK) return s;
+    return MGG_OK;
+}
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+static void export_groups(const std::vector<int32_t> &rp, int32_t ps, int32_t *row, int32_t *start, int32_t *end)
+{
+    int64_t g = 0;
+    for (size_t r = 0; r + 1 < rp.size(); ++r)
+        for (int32_t s = rp[r]; s < rp[r + 1]; s += ps, ++g) {
+            if (row) row[g] = static_cast<int32_t>(r);
+            if (start) start[g] = s;
+            if (end) end[g] = std::min<int32_t>(s + ps, rp[r + 1]);
+        }
+}
+
+template <typename T>
+static void copy_out(const std::vector<T> &v, T *dst)
+{
+    if (dst && !v.empty()) std::memcpy(dst, v.data(), v.size() * sizeof(T));
+}
+
+
+}  // namespace mgg
+
+using namespace mgg;
+
+extern "C" {
+
+const char *mgg_last_error(void) { return mgg::last_error(); }
+const char *mgg_version(void) { return "mgg-mi355x 0.1 (gfx950)"; }
+
+mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, const int32_t *col_idx,
+                                 int32_t num_parts, int32_t part_id, const int64_t *bounds,
+                                 const mgg_build_opts_t *opts, mgg_partition_t **out)
+{
+    if (!out) return fail(MGG_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (num_nodes < 0 || !row_ptr) return fail(MGG_ERR_INVALID_ARG, "num_nodes < 0 or row_ptr is NULL");
+    if (num_nodes > INT32_MAX - 1) return fail(MGG_ERR_UNSUPPORTED, "more than 2^31-2 nodes");
+    if (num_parts < 1 || part_id < 0 || part_id >= num_parts)
+        return fail(MGG_ERR_INVALID_ARG, "part_id %d outside [0, %d)", part_id, num_parts);
+    int32_t ps = 32, dist = 16, short_max = 16, host_only = 0;
+    if (opts) {
+        if (opts->ps) ps = opts->ps;
+        if (opts->dist) dist = opts->dist;
+        if (opts->short_max) short_max = opts->short_max;
+        host_only = opts->host_only;
+    }
+    if (ps < 1 || ps > 64) return fail(MGG_ERR_INVALID_ARG, "ps %d outside [1, 64]", ps);
+    if (dist < 1 || dist > 1024) return fail(MGG_ERR_INVALID_ARG, "dist %d outside [1, 1024]", dist);
+    if (short_max > 4096) return fail(MGG_ERR_INVALID_ARG, "short_max %d above 4096", short_max);
+
+    // ---- validate the graph ------------------------------------------------------------
+    if (row_ptr[0] != 0) return fail(MGG_ERR_BAD_GRAPH, "row_ptr[0] != 0");
+    for (int64_t v = 0; v < num_nodes; ++v)
+        if (row_ptr[v + 1] < row_ptr[v]) return fail(MGG_ERR_BAD_GRAPH, "row_ptr decreases at row %lld", (long long)v);
+    const int64_t nnz = row_ptr[num_nodes];
+    if (nnz > 0 && !col_idx) return fail(MGG_ERR_INVALID_ARG, "col_idx is NULL");
+    for (int64_t e = 0; e < nnz; ++e)
+        if (col_idx[e] < 0 || col_idx[e] >= num_nodes)
+            return fail(MGG_ERR_BAD_GRAPH, "column %d at position %lld outside [0, %lld)", col_idx[e],
+                        (long long)e, (long long)num_nodes);
+
+    // ---- node range --------------------------------------------------------------------
+    std::vector<int64_t> bnd(num_parts + 1);
+    if (bounds) {
+        for (int32_t q = 0; q <= num_parts; ++q) bnd[q] = bounds[q];
+        if (bnd[0] != 0 || bnd[num_parts] != num_nodes)
+            return fail(MGG_ERR_INVALID_ARG, "bounds must run from 0 to num_nodes");
+        for (int32_t q = 0; q < num_parts; ++q)
+            if (bnd[q + 1] < bnd[q]) return fail(MGG_ERR_INVALID_ARG, "bounds decrease at part %d", q);
+    } else {
+        for (int32_t q = 0; q <= num_parts; ++q) bnd[q] = (num_nodes * q) / num_parts;
+    }
+    const int64_t lb = bnd[part_id], ub = bnd[part_id + 1], n_own = ub - lb;
+    if (row_ptr[ub] - row_ptr[lb] >= INT32_MAX)
+        return fail(MGG_ERR_UNSUPPORTED, "this share holds 2^31-1 or more neighbours");
+
+    mgg_partition *p = new (std::nothrow) mgg_partition;
+    if (!p) return fail(MGG_ERR_ALLOC, "out of host memory");
+    try {
+        p->num_nodes = num_nodes; p->lb = lb; p->ub = ub; p->n_own = n_own;
+        p->num_parts = num_parts; p->part_id = part_id;
+        p->ps = ps; p->dist = dist; p->short_max = short_max;
+
+        // ---- pass 1: count local / remote per owned row, mark halo nodes -----------------
+        std::vector<uint8_t> is_halo(static_cast<size_t>(num_nodes), 0);
+        p->local_row_ptr.assign(n_own + 1, 0);
+        p->remote_row_ptr.assign(n_own + 1, 0);
+        for (int64_t v = 0; v < n_own; ++v) {
+            const int64_t g = lb + v;
+            int32_t nl = 0, nr = 0;
+            for (int64_t e = row_ptr[g]; e < row_ptr[g + 1]; ++e) {
+                const int64_t u = col_idx[e];
+                if (u == g) continue;                       // self term comes from the mode
+                if (u >= lb && u < ub) ++nl;
+                else { ++nr; is_halo[u] = 1; }
+            }
+            p->local_row_ptr[v + 1] = p->local_row_ptr[v] + nl;
+            p->remote_row_ptr[v + 1] = p->remote_row_ptr[v] + nr;
+        }
+        // ---- halo list in ascending global id and the id -> slot map ---------------------
+        std::vector<int32_t> slot_of(static_cast<size_t>(num_nodes), -1);
+        for (int64_t u = 0; u < num_nodes; ++u)
+            if (is_halo[u]) { slot_of[u] = static_cast<int32_t>(p->halo_gid.size()); p->halo_gid.push_back(static_cast<int32_t>(u)); }
+        is_halo.clear(); is_halo.shrink_to_fit();
+        const int64_t num_halo = static_cast<int64_t>(p->halo_gid.size());
+        p->halo_peer_ptr.assign(num_parts + 1, 0);
+        for (int32_t q = 0; q <= num_parts; ++q)
+            p->halo_peer_ptr[q] = std::lower_bound(p->halo_gid.begin(), p->halo_gid.end(), bnd[q],
+                                                   [](int32_t gid, int64_t b) { return gid < b; }) - p->halo_gid.begin();
+
+        // ---- pass 2: fill the two column arrays -----------------------------------------
+        p->local_col.resize(p->local_row_ptr[n_own]);
+        p->remote_col.resize(p->remote_row_ptr[n_own]);
+        for (int64_t v = 0; v < n_own; ++v) {
+            const int64_t g = lb + v;
+            int32_t wl = p->local_row_ptr[v], wr = p->remote_row_ptr[v];
+            for (int64_t e = row_ptr[g]; e < row_ptr[g + 1]; ++e) {
+                const int64_t u = col_idx[e];
+                if (u == g) continue;
+                if (u >= lb && u < ub) p->local_col[wl++] = static_cast<int32_t>(u - lb);
+                else p->remote_col[wr++] = slot_of[u];
+            }
+        }
+        slot_of.clear(); slot_of.shrink_to_fit();
+
+        // ---- whole-graph degrees and 1/sqrt(deg+1) ---------------------------------------
+        auto degree_of = [&](int64_t g) {
+            int32_t d = static_cast<int32_t>(row_ptr[g + 1] - row_ptr[g]);
+            for (int64_t e = row_ptr[g]; e < row_ptr[g + 1]; ++e) d -= (col_idx[e] == g);
+            return d;
+        };
+        p->deg_own.resize(n_own); p->dinv_own.resize(n_own);
+        for (int64_t v = 0; v < n_own; ++v) {
+            p->deg_own[v] = degree_of(lb + v);
+            p->dinv_own[v] = static_cast<float>(1.0 / std::sqrt(static_cast<double>(p->deg_own[v]) + 1.0));
+        }
+        p->deg_halo.resize(num_halo); p->dinv_halo.resize(num_halo);
+        for (int64_t h = 0; h < num_halo; ++h) {
+            p->deg_halo[h] = degree_of(p->halo_gid[h]);
+            p->dinv_halo[h] = static_cast<float>(1.0 / std::sqrt(static_cast<double>(p->deg_halo[h]) + 1.0));
+        }
+
+        // ---- work decomposition ----------------------------------------------------------
+        // short rows: several per wavefront; whole rows: one item; long rows: cut at
+        // multiples of dist neighbour partitions, item k pairing local run k with remote run k.
+        const int64_t run = static_cast<int64_t>(ps) * dist;   // neighbours per run
+        std::vector<WorkItem> whole;
+        std::vector<std::vector<int32_t>> by_len(short_max >= 0 ? short_max + 1 : 0);
+        for (int64_t v = 0; v < n_own; ++v) {
+            const int32_t l0 = p->local_row_ptr[v], l1 = p->local_row_ptr[v + 1];
+            const int32_t r0 = p->remote_row_ptr[v], r1 = p->remote_row_ptr[v + 1];
+            const int64_t dl = l1 - l0, dr = r1 - r0;
+            p->n_groups_local += ceil_div(dl, ps);
+            p->n_groups_remote += ceil_div(dr, ps);
+            if (short_max >= 0 && dl + dr <= short_max) { by_len[dl + dr].push_back(static_cast<int32_t>(v)); continue; }
+            const int64_t n_it = std::max<int64_t>(1, std::max(ceil_div(dl, run), ceil_div(dr, run)));
+            if (n_it == 1) {
+                whole.push_back(WorkItem{static_cast<int32_t>(v), l0, l1, r0, r1, -1, 0, 0});
+                continue;
+            }
+            SplitRow sr{static_cast<int32_t>(v), static_cast<int32_t>(p->n_split_items), static_cast<int32_t>(n_it), 0};
+            p->split_rows.push_back(sr);
+            for (int64_t k = 0; k < n_it; ++k) {
+                WorkItem it;
+                it.row = static_cast<int32_t>(v);
+                it.lbeg = static_cast<int32_t>(std::min<int64_t>(l0 + k * run, l1));
+                it.lend = static_cast<int32_t>(std::min<int64_t>(l0 + (k + 1) * run, l1));
+                it.rbeg = static_cast<int32_t>(std::min<int64_t>(r0 + k * run, r1));
+                it.rend = static_cast<int32_t>(std::min<int64_t>(r0 + (k + 1) * run, r1));
+                it.slot = static_cast<int32_t>(p->n_split_items++);
+                it.pad0 = it.pad1 = 0;
+                p->items.push_back(it);                    // heavy items go first in launch order
+            }
+        }
+        p->items.insert(p->items.end(), whole.begin(), whole.end());
+        for (int32_t len = short_max; len >= 0; --len)         // longest first, isolated rows last
+            p->short_rows.insert(p->short_rows.end(), by_len[len].begin(), by_len[len].end());
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return fail(MGG_ERR_ALLOC, "out of host memory while building the partition");
+    }
+
+    if (!host_only) {
+        mgg_status_t s = upload_all(p);
+        if (s != MGG_OK) { free_device(p); delete p; return s; }
+    }
+    *out = p;
+    return MGG_OK;
+}
+
+mgg_status_t mgg_partition_info(const mgg_partition_t *p, mgg_partition_info_t *o)
+{
+    if (!p || !o) return fail(MGG_ERR_INVALID_ARG, "NULL argument");
+    std::memset(o, 0, sizeof *o);
+    o->num_nodes = p->num_nodes; o->lb = p->lb; o->ub = p->ub; o->n_own = p->n_own;
+    o->nnz_local = static_cast<int64_t>(p->local_col.size());
+    o->nnz_remote = static_cast<int64_t>(p->remote_col.size());
+    o->num_halo = static_cast<int64_t>(p->halo_gid.size());
+    o->num_parts = p->num_parts; o->part_id = p->part_id;
+    o->ps = p->ps; o->dist = p->dist; o->short_max = p->short_max; o->on_device = p->device >= 0;
+    o->n_groups_local = p->n_groups_local; o->n_groups_remote = p->n_groups_remote;
+    o->n_short_rows = static_cast<int64_t>(p->short_rows.size());
+    o->n_items = static_cast<int64_t>(p->items.size());
+    o->n_split_rows = static_cast<int64_t>(p->split_rows.size());
+    o->n_split_items = p->n_split_items;
+    return MGG_OK;
+}
+
+mgg_status_t mgg_partition_export(const mgg_partition_t *p, mgg_partition_arrays_t *a)
+{
+    if (!p || !a) return fail(MGG_ERR_INVALID_ARG, "NULL argument");
+    copy_out(p->local_row_ptr, a->local_row_ptr);
+    copy_out(p->local_col, a->local_col);
+    copy_out(p->remote_row_ptr, a->remote_row_ptr);
+    copy_out(p->remote_col, a->remote_col);
+    copy_out(p->halo_gid, a->halo_gid);
+    copy_out(p->halo_peer_ptr, a->halo_peer_ptr);
+    copy_out(p->deg_own, a->deg_own);
+    copy_out(p->deg_halo, a->deg_halo);
+    if (a->grp_local_row || a->grp_local_start || a->grp_local_end)
+        export_groups(p->local_row_ptr, p->ps, a->grp_local_row, a->grp_local_start, a->grp_local_end);
+    if (a->grp_remote_row || a->grp_remote_start || a->grp_remote_end)
+        export_groups(p->remote_row_ptr, p->ps, a->grp_remote_row, a->grp_remote_start, a->grp_remote_end);
+    copy_out(p->short_rows, a->short_rows);
+    for (size_t i = 0; i < p->items.size(); ++i) {
+        const WorkItem &it = p->items[i];
+        if (a->item_row) a->item_row[i] = it.row;
+        if (a->item_lbeg) a->item_lbeg[i] = it.lbeg;
+        if (a->item_lend) a->item_lend[i] = it.lend;
+        if (a->item_rbeg) a->item_rbeg[i] = it.rbeg;
+        if (a->item_rend) a->item_rend[i] = it.rend;
+        if (a->item_slot) a->item_slot[i] = it.slot;
+    }
+    return MGG_OK;
+}
+
+void mgg_partition_destroy(mgg_partition_t *p)
+{
+    if (!p) return;
+    if (p->device >= 0) {
+        int cur = 0;
+        bool switched = hipGetDevice(&cur) == hipSuccess && cur != p->device && hipSetDevice(p->device) == hipSuccess;
+        free_device(p);
+        if (switched) (void)hipSetDevice(cur);
+    }
+    delete p;
+}
+
+mgg_status_t mgg_split_edge_balanced(int64_t num_nodes, const int64_t *row_ptr, int32_t num_parts,
+                                     int64_t *bounds_out)
+{
+    if (num_nodes < 0 || !row_ptr || num_parts < 1 || !bounds_out)
+        return fail(MGG_ERR_INVALID_ARG, "bad argument");
+    const int64_t e_total = row_ptr[num_nodes];
+    const int64_t per_gpu = ceil_div(e_total, num_parts);
+    const int64_t *first = row_ptr, *last = row_ptr + num_nodes + 1;
+    int64_t prev = 0;
+    bounds_out[0] = 0;
+    for (int32_t s = 1; s < num_parts; ++s) {
+        const int64_t target = std::min(row_ptr[prev] + per_gpu, e_total);
+        // binary search restricted to [prev, N]: first node whose edge offset reaches target
+        prev = std::lower_bound(first + prev, last, target) - first;
+        prev = std::min(prev, num_nodes);
+        bounds_out[s] = prev;
+    }
+    bounds_out[num_parts] = num_nodes;
+    return MGG_OK;
+}
+
+}  // extern "C"

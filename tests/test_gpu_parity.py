@@ -1,0 +1,304 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the C ABI.
+
+Tolerances (written out here, derived in the design doc):
+  fp32 aggregation ........ |gpu - ref| <= 1e-6 + 1e-4 |ref|
+  bf16-input aggregation .. |gpu - ref| <= 2e-2 |ref| + 1e-2 max|ref|   (and, tighter, the fp32
+                            accumulation bound 1e-5 * sum|w x| since bf16 inputs are exact in fp32)
+  fp32 Update ............. |gpu - ref| <= 1e-4 |ref| + 2 K 2^-24 (|a| @ |w|)
+  bf16 Update / layers .... |gpu - ref| <= 2e-2 |ref| + 2^-7 (|a| @ |w|)
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2209_06800_amd import binding, inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+# ----------------------------------------------------------------------------- helpers
+def to_dev(a: np.ndarray):
+    """numpy fp32 / bf16-bit array -> torch tensor on the GPU (bf16 bits are reinterpreted)."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16).copy()).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def to_host64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def assert_close(got, ref, rtol, atol, what=""):
+    got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite output"
+    err = np.abs(got - ref)
+    bound = atol + rtol * np.abs(ref)
+    bad = err > bound
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - bound), err.shape)
+        raise AssertionError(f"{what}: {bad.sum()} of {bad.size} elements out of tolerance; worst at {i}: "
+                             f"got {got[i]!r} ref {ref[i]!r} err {err[i]:.3e} bound {np.broadcast_to(bound, err.shape)[i]:.3e}")
+
+
+def agg_tolerances(dtype):
+    return (1e-4, 1e-6) if dtype == "f32" else (2e-2, None)
+
+
+def check_aggregate(w_row_ptr, w_col, parts, part_id, bounds, x, mode, eps=0.0, build=None, ld_pad=0,
+                    misalign=0, rows=None, what=""):
+    """Run mgg_aggregate on one share and compare every (or the sampled) output row."""
+    build = build or {}
+    ref_part = oracle.build_partition(w_row_ptr, w_col, parts, part_id, bounds)
+    lb, ub, hg = ref_part["lb"], ref_part["ub"], ref_part["halo_gid"]
+    part = binding.mgg_build_partition(w_row_ptr, w_col, parts, part_id, bounds, **build)
+    x_local_np, x_halo_np = x[lb:ub], x[hg]
+    dim = x.shape[1]
+
+    def place(a):
+        """Device copy with optional row padding and a base pointer that is not 16-byte aligned."""
+        t = to_dev(a)
+        if ld_pad or misalign:
+            buf = torch.zeros(a.shape[0] * (dim + ld_pad) + misalign, dtype=t.dtype, device=DEV)
+            view = buf[misalign:].view(a.shape[0], dim + ld_pad)[:, :dim]
+            view.copy_(t)
+            return view
+        return t
+
+    xl, xh = place(x_local_np), (place(x_halo_np) if hg.size else None)
+    out = torch.full((ub - lb, dim + ld_pad), float("nan"), dtype=torch.float32, device=DEV)[:, :dim]
+    binding.mgg_aggregate(part, mode, xl, xh, eps=eps, out=out)
+    torch.cuda.synchronize()
+    got = to_host64(out)
+    ref = oracle.aggregate(w_row_ptr, w_col, mode, x_local_np, lb=lb, ub=ub, x_halo=x_halo_np, halo_gid=hg,
+                           eps=eps, rows=rows)
+    if rows is not None:
+        got = got[np.asarray(rows)]
+    is_bf16 = x.dtype == np.uint16
+    if is_bf16:
+        assert_close(got, ref, 2e-2, 1e-2 * max(np.abs(ref).max(), 1e-30), what)
+        # tighter: fp32 accumulation of exact inputs; scale = sum |w x| per output element
+        scale = oracle.aggregate(w_row_ptr, w_col, mode, np.abs(inputs.bf16_bits_to_f32(x_local_np)), lb=lb, ub=ub,
+                                 x_halo=np.abs(inputs.bf16_bits_to_f32(x_halo_np)), halo_gid=hg, eps=abs(eps), rows=rows)
+        assert np.all(np.abs(got - ref) <= 1e-5 * scale + 1e-30), f"{what}: beyond the fp32 accumulation bound"
+    else:
+        assert_close(got, ref, 1e-4, 1e-6, what)
+    part.destroy()
+    return got
+
+
+def small_rmat(scale=12, draws=60000, seed=0):
+    rng = np.random.default_rng(seed)
+    row_ptr, col = inputs.rmat_graph(scale, draws, 0.57, 0.19, 0.19, 0.05, rng)
+    return row_ptr, col, rng
+
+
+# ----------------------------------------------------------------------------- aggregation
+@pytest.mark.parametrize("dim", [1, 3, 4, 16, 20, 47, 64, 100, 128, 256, 260, 602, 608, 1024])
+@pytest.mark.parametrize("mode", ["gcn", "gin"])
+def test_aggregate_fp32_dims(dim, mode):
+    row_ptr, col, rng = small_rmat(seed=dim)
+    n = row_ptr.size - 1
+    x = rng.standard_normal((n, dim)).astype(np.float32)
+    bounds = inputs.equal_node_bounds(n, 4)
+    check_aggregate(row_ptr, col, 4, 0, bounds, x, mode, eps=0.25, what=f"f32 dim {dim} {mode}")
+
+
+@pytest.mark.parametrize("dim", [1, 2, 8, 24, 30, 64, 128, 129, 136, 520])
+def test_aggregate_bf16_dims(dim):
+    row_ptr, col, rng = small_rmat(seed=1000 + dim)
+    n = row_ptr.size - 1
+    x = inputs.to_bf16_bits(rng.standard_normal((n, dim)).astype(np.float32))
+    bounds = inputs.equal_node_bounds(n, 8)
+    check_aggregate(row_ptr, col, 8, 0, bounds, x, "gin", what=f"bf16 dim {dim} gin")
+    check_aggregate(row_ptr, col, 8, 3, bounds, x, "gcn", what=f"bf16 dim {dim} gcn")
+
+
+@pytest.mark.parametrize("build", [dict(ps=1, dist=1), dict(ps=2, dist=3), dict(ps=7, dist=2), dict(ps=32, dist=1),
+                                   dict(ps=64, dist=4), dict(ps=32, dist=1024), dict(short_max=-1),
+                                   dict(short_max=4096), dict(ps=5, dist=5, short_max=3)])
+def test_every_schedule_gives_the_same_answer(build):
+    """Neighbour-partition size, pairs per work item and the short-row bin change only the
+    schedule (section 4.1 Step-3, section 5.1), never the value."""
+    row_ptr, col, rng = small_rmat(seed=77)
+    n = row_ptr.size - 1
+    x = rng.standard_normal((n, 64)).astype(np.float32)
+    bounds = inputs.equal_node_bounds(n, 4)
+    for p in (0, 2):
+        check_aggregate(row_ptr, col, 4, p, bounds, x, "gcn", build=build, what=f"{build} part {p}")
+    xb = inputs.to_bf16_bits(x[:, :40])
+    check_aggregate(row_ptr, col, 4, 1, bounds, xb, "gin", eps=-0.5, build=build, what=f"{build} bf16")
+
+
+@pytest.mark.parametrize("ld_pad,misalign", [(0, 1), (3, 0), (4, 0), (5, 2), (8, 4)])
+def test_padded_rows_and_unaligned_base(ld_pad, misalign):
+    row_ptr, col, rng = small_rmat(scale=11, draws=30000, seed=5)
+    n = row_ptr.size - 1
+    bounds = inputs.equal_node_bounds(n, 2)
+    for dim in (64, 100):
+        x = rng.standard_normal((n, dim)).astype(np.float32)
+        check_aggregate(row_ptr, col, 2, 1, bounds, x, "gcn", ld_pad=ld_pad, misalign=misalign,
+                        what=f"dim {dim} pad {ld_pad} misalign {misalign}")
+    xb = inputs.to_bf16_bits(rng.standard_normal((n, 128)).astype(np.float32))
+    check_aggregate(row_ptr, col, 2, 0, bounds, xb, "gin", ld_pad=ld_pad, misalign=misalign, what="bf16 padded")
+
+
+def test_degenerate_graphs():
+    rng = np.random.default_rng(3)
+    # no edges at all: every row is its own embedding (times 1 + eps for GIN)
+    n = 300
+    row_ptr, col = np.zeros(n + 1, dtype=np.int64), np.zeros(0, dtype=np.int32)
+    x = rng.standard_normal((n, 64)).astype(np.float32)
+    got = check_aggregate(row_ptr, col, 1, 0, np.array([0, n]), x, "gcn", what="edgeless gcn")
+    assert np.array_equal(got.astype(np.float32), x)
+    check_aggregate(row_ptr, col, 1, 0, np.array([0, n]), x, "gin", eps=0.5, what="edgeless gin")
+    # star: one row with n-1 neighbours (cut into many items), n-1 rows with one
+    n = 5000
+    adj = [list(range(1, n))] + [[0]] * (n - 1)
+    row_ptr, col = inputs.csr_from_adjacency_lists(adj)
+    x = rng.standard_normal((n, 32)).astype(np.float32)
+    check_aggregate(row_ptr, col, 1, 0, np.array([0, n]), x, "gcn", what="star")
+    check_aggregate(row_ptr, col, 2, 0, np.array([0, 1, n]), x, "gin", what="star centre, all remote")
+    check_aggregate(row_ptr, col, 2, 1, np.array([0, 1, n]), x, "gcn", what="star leaves, one halo row")
+    # an empty node range is a no-op
+    part = binding.mgg_build_partition(row_ptr, col, 3, 1, [0, 10, 10, n])
+    out = binding.mgg_aggregate(part, "gcn", torch.zeros((0, 32), device=DEV), torch.zeros((4, 32), device=DEV))
+    assert out.shape == (0, 32)
+    # self-loops and duplicate neighbours in the input
+    row_ptr, col = inputs.csr_from_adjacency_lists([[0, 1, 1, 2], [0], [0, 2]])
+    x = rng.standard_normal((3, 16)).astype(np.float32)
+    check_aggregate(row_ptr, col, 1, 0, np.array([0, 3]), x, "gcn", what="self-loops gcn")
+    check_aggregate(row_ptr, col, 1, 0, np.array([0, 3]), x, "gin", what="self-loops gin")
+
+
+def test_partition_consistency_on_the_gpu():
+    """All shares, one after another, reproduce the single-partition result (whole-graph degrees)."""
+    row_ptr, col, rng = small_rmat(seed=9)
+    n = row_ptr.size - 1
+    x = rng.standard_normal((n, 48)).astype(np.float32)
+    whole = check_aggregate(row_ptr, col, 1, 0, np.array([0, n]), x, "gcn")
+    for parts in (3, 8):
+        bounds = inputs.equal_node_bounds(n, parts)
+        pieces = [check_aggregate(row_ptr, col, parts, p, bounds, x, "gcn") for p in range(parts)]
+        np.testing.assert_allclose(np.concatenate(pieces), whole, rtol=2e-4, atol=2e-6)
+
+
+def test_results_do_not_depend_on_scheduling():
+    """Partial sums of split rows are combined in a fixed order: two runs agree bit for bit."""
+    w = inputs.config(2, shrink=6)
+    part = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
+    ref_part = oracle.build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
+    xl, xh = to_dev(w.x[w.lb:w.ub]), to_dev(w.x[ref_part["halo_gid"]])
+    a = binding.mgg_aggregate(part, "gcn", xl, xh).clone()
+    for _ in range(3):
+        b = binding.mgg_aggregate(part, "gcn", xl, xh)
+        assert torch.equal(a, b)
+
+
+# ----------------------------------------------------------------------------- update
+def update_bound(a64, w64, k, bf16):
+    s = np.abs(a64) @ np.abs(w64)
+    return (2.0 ** -7) * s if bf16 else 2.0 * k * 2.0 ** -24 * s
+
+
+@pytest.mark.parametrize("n_rows,d_in,d_out", [(1, 1, 1), (127, 16, 16), (129, 64, 64), (1000, 100, 256),
+                                               (333, 602, 256), (4096, 256, 47), (77, 33, 300), (500, 5, 513)])
+@pytest.mark.parametrize("act", ["none", "relu"])
+def test_update_fp32(n_rows, d_in, d_out, act):
+    rng = np.random.default_rng(n_rows + d_in)
+    a = rng.standard_normal((n_rows, d_in)).astype(np.float32)
+    w = (0.1 * rng.standard_normal((d_in, d_out))).astype(np.float32)
+    b = rng.standard_normal(d_out).astype(np.float32)
+    for bias in (None, b):
+        got = binding.mgg_update(to_dev(a), to_dev(w), None if bias is None else to_dev(bias), act)
+        torch.cuda.synchronize()
+        ref = oracle.update(a, w, bias, act)
+        bound = update_bound(a.astype(np.float64), w.astype(np.float64), d_in, False)
+        assert_close(to_host64(got), ref, 1e-4, bound, f"update f32 {n_rows}x{d_in}x{d_out} {act}")
+
+
+def test_update_fp32_padded_and_unaligned_input():
+    rng = np.random.default_rng(12)
+    a = rng.standard_normal((300, 602)).astype(np.float32)
+    w = (0.1 * rng.standard_normal((602, 64))).astype(np.float32)
+    buf = torch.zeros(300 * 603 + 1, device=DEV)
+    av = buf[1:].view(300, 603)[:, :602]
+    av.copy_(to_dev(a))
+    out = torch.full((300, 70), float("nan"), device=DEV)[:, :64]
+    binding.mgg_update(av, to_dev(w), None, "relu", out=out)
+    ref = oracle.update(a, w, None, "relu")
+    assert_close(to_host64(out), ref, 1e-4, update_bound(a.astype(np.float64), w.astype(np.float64), 602, False), "padded update")
+
+
+@pytest.mark.parametrize("n_rows,d_in,d_out", [(1, 8, 8), (200, 128, 128), (1025, 64, 47), (300, 100, 130), (64, 7, 5)])
+@pytest.mark.parametrize("a_is_bf16", [False, True])
+def test_update_bf16(n_rows, d_in, d_out, a_is_bf16):
+    rng = np.random.default_rng(n_rows * 7 + d_out)
+    a32 = rng.standard_normal((n_rows, d_in)).astype(np.float32)
+    wb = inputs.to_bf16_bits((0.1 * rng.standard_normal((d_in, d_out))).astype(np.float32))
+    a_in = inputs.to_bf16_bits(a32) if a_is_bf16 else a32
+    ref = oracle.update(a_in, wb, None, "relu")
+    s_bound = update_bound(oracle.to_f64(a_in), oracle.to_f64(wb), d_in, True)
+    for out_dtype in (torch.float32, torch.bfloat16):
+        got = binding.mgg_update(to_dev(a_in), to_dev(wb), None, "relu", out_dtype=out_dtype)
+        torch.cuda.synchronize()
+        assert_close(to_host64(got), ref, 2e-2, s_bound, f"update bf16 {n_rows}x{d_in}x{d_out} a_bf16={a_is_bf16}")
+
+
+# ----------------------------------------------------------------------------- whole layers on the five configs
+SHRINK = {1: 0, 2: 5, 3: 7, 4: 4, 5: 6}
+
+
+def run_config_layers(w: inputs.Workload, rows=None):
+    """Forward of every layer of a workload on the GPU and in the oracle; returns max errors."""
+    ref_part = oracle.build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
+    lb, ub, hg = ref_part["lb"], ref_part["ub"], ref_part["halo_gid"]
+    part = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
+    assert part.info.num_halo == hg.size and part.info.n_own == ub - lb
+    x_local, x_halo = w.x[lb:ub], w.x[hg]
+    bf16 = w.dtype == "bf16"
+    d_x_local, d_x_halo = to_dev(x_local), (to_dev(x_halo) if hg.size else None)
+    h_ref_local = None
+    for li, layer in enumerate(w.layers):
+        if li == 1:
+            # second layer of the 2-layer config: owned rows = layer-1 output; halo rows = seeded stand-in
+            x_halo = inputs.layer2_halo_table(w.notes["layer2_halo_seed"], hg.size, layer.dims[0])
+            x_local = h_gpu_np                                   # what the GPU produced for layer 1
+            d_x_local, d_x_halo = h_gpu, to_dev(x_halo)
+        dw = [to_dev(m) for m in layer.weights]
+        h_gpu = binding.mgg_layer_forward(part, layer.mode, d_x_local, d_x_halo, dw, layer.acts, eps=layer.eps)
+        torch.cuda.synchronize()
+        h_gpu_np = h_gpu.float().cpu().numpy()
+        ref = oracle.layer_forward(w.row_ptr, w.col, layer.mode, x_local, layer.weights, layer.acts, eps=layer.eps,
+                                   lb=lb, ub=ub, x_halo=x_halo, halo_gid=hg, rows=rows)
+        # error scale: |agg| @ |W| chained through the linears
+        agg = oracle.aggregate(w.row_ptr, w.col, layer.mode, x_local, lb=lb, ub=ub, x_halo=x_halo, halo_gid=hg,
+                               eps=layer.eps, rows=rows)
+        s = np.abs(agg)
+        for m in layer.weights:
+            s = s @ np.abs(oracle.to_f64(m))
+        k = max(layer.dims[:-1])
+        bound = (2.0 ** -6) * s if bf16 else 2e-6 * s + 2.0 * k * 2.0 ** -24 * s
+        got = h_gpu_np.astype(np.float64)
+        if rows is not None:
+            got = got[np.asarray(rows)]
+        assert_close(got, ref, 2e-2 if bf16 else 1e-4, bound, f"{w.name} layer {li}")
+    part.destroy()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_layers_of_the_five_configs_scaled(cfg):
+    run_config_layers(inputs.config(cfg, shrink=SHRINK[cfg]))
+
+
+def test_aggregate_cfg2_full_size_sampled_rows():
+    """The bench workload at full size, in the launch configuration bench.py times; the oracle
+    recomputes a sample of rows (every degree class, plus the heaviest rows)."""
+    w = inputs.config(2)
+    deg = np.diff(w.row_ptr)[w.lb:w.ub]
+    rng = np.random.default_rng(1)
+    heavy = np.argsort(deg)[-8:]
+    sample = np.unique(np.concatenate([heavy, rng.integers(0, w.ub - w.lb, 400), np.nonzero(deg == 0)[0][:8]]))
+    check_aggregate(w.row_ptr, w.col, w.parts, w.part_id, w.bounds, w.x, "gcn", rows=sample, what="cfg2 full")

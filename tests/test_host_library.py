@@ -1,0 +1,195 @@
+"""CPU-only checks of libmgg: the library loads and exports every symbol the header declares,
+the host partition builder agrees bit for bit with the oracle's independent builder, work
+items form a valid schedule, and bad arguments come back as error codes."""
+import ctypes
+import json
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2209_06800_amd import binding, inputs
+from paper_2209_06800_amd.binding import MggError
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "mgg.h")).read()
+    declared = set(re.findall(r"\b(mgg_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTED_SYMBOLS)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert "gfx950" in binding.mgg_version()
+
+
+def _compare_with_oracle(row_ptr, col, parts, p, bounds, **opts):
+    want = oracle.build_partition(row_ptr, col, parts, p, bounds)
+    part = binding.mgg_build_partition(row_ptr, col, parts, p, bounds, host_only=True, **opts)
+    got = part.export()
+    info = part.info
+    assert (info.lb, info.ub, info.n_own) == (want["lb"], want["ub"], want["n_own"])
+    assert info.on_device == 0
+    for key in ("local_row_ptr", "local_col", "remote_row_ptr", "remote_col", "halo_gid", "halo_peer_ptr",
+                "deg_own", "deg_halo"):
+        assert np.array_equal(got[key].astype(np.int64), want[key].astype(np.int64)), key
+    for kind in ("local", "remote"):
+        row, start, end = oracle.neighbor_groups(want[f"{kind}_row_ptr"], info.ps)
+        assert np.array_equal(got[f"grp_{kind}_row"], row)
+        assert np.array_equal(got[f"grp_{kind}_start"], start)
+        assert np.array_equal(got[f"grp_{kind}_end"], end)
+    _check_schedule(got, info)
+    part.destroy()
+    return got, info
+
+
+def _check_schedule(got, info):
+    """Several schedules are valid; check that this one covers every neighbour exactly once,
+    cuts rows only at multiples of ps * dist, and uses each scratch slot once."""
+    n_own = info.n_own
+    lrp, rrp = got["local_row_ptr"], got["remote_row_ptr"]
+    deg = np.diff(lrp) + np.diff(rrp)
+    seen_rows = np.zeros(n_own, dtype=np.int64)
+    np.add.at(seen_rows, got["short_rows"], 1)
+    if info.short_max >= 0:
+        assert np.all(deg[got["short_rows"]] <= info.short_max)
+        assert np.all(np.diff(deg[got["short_rows"]]) <= 0)            # longest first
+    run = info.ps * info.dist
+    cover_l = np.zeros(n_own, dtype=np.int64)
+    cover_r = np.zeros(n_own, dtype=np.int64)
+    rows = got["item_row"]
+    np.add.at(cover_l, rows, got["item_lend"] - got["item_lbeg"])
+    np.add.at(cover_r, rows, got["item_rend"] - got["item_rbeg"])
+    item_rows = np.unique(rows)
+    seen_rows[item_rows] += 1
+    assert np.all(seen_rows == 1)                                      # every row in exactly one bin
+    assert np.array_equal(cover_l[item_rows], np.diff(lrp)[item_rows])
+    assert np.array_equal(cover_r[item_rows], np.diff(rrp)[item_rows])
+    empty_l, empty_r = got["item_lbeg"] == got["item_lend"], got["item_rbeg"] == got["item_rend"]
+    assert np.all(((got["item_lbeg"] - lrp[rows]) % run == 0) | empty_l)   # cuts at partition-run boundaries
+    assert np.all(((got["item_rbeg"] - rrp[rows]) % run == 0) | empty_r)
+    assert np.all(got["item_lend"] - got["item_lbeg"] <= run) and np.all(got["item_rend"] - got["item_rbeg"] <= run)
+    assert np.all(got["item_lbeg"] >= lrp[rows]) and np.all(got["item_lend"] <= lrp[rows + 1])
+    assert np.all(got["item_rbeg"] >= rrp[rows]) and np.all(got["item_rend"] <= rrp[rows + 1])
+    slots = got["item_slot"]
+    whole = slots < 0
+    counts = np.bincount(rows, minlength=n_own)
+    assert np.all(counts[rows[whole]] == 1) and np.all(counts[rows[~whole]] > 1)
+    assert np.array_equal(np.sort(slots[~whole]), np.arange(info.n_split_items))
+    assert info.n_split_rows == np.unique(rows[~whole]).size
+    assert info.n_groups_local == int(np.sum(-(-np.diff(lrp) // info.ps)))
+    assert info.n_groups_remote == int(np.sum(-(-np.diff(rrp) // info.ps)))
+
+
+def test_partition_matches_hand_written_fixture():
+    fx = json.load(open(os.path.join(GOLDEN, "tiny_partition.json")))
+    row_ptr, col = inputs.csr_from_adjacency_lists(fx["adjacency"])
+    for p, want in enumerate(fx["parts"]):
+        part = binding.mgg_build_partition(row_ptr, col, 2, p, fx["bounds"], ps=2, host_only=True)
+        got = part.export()
+        for key in ("local_row_ptr", "local_col", "remote_row_ptr", "remote_col", "halo_gid", "halo_peer_ptr",
+                    "deg_own", "deg_halo"):
+            assert got[key].tolist() == want[key], (p, key)
+        for kind in ("local", "remote"):
+            g = want[f"groups_ps2_{kind}"]
+            assert got[f"grp_{kind}_row"].tolist() == g["row"]
+            assert got[f"grp_{kind}_start"].tolist() == g["start"]
+            assert got[f"grp_{kind}_end"].tolist() == g["end"]
+
+
+@pytest.mark.parametrize("parts,ps,dist,short_max", [(1, 0, 0, 0), (4, 32, 16, 16), (4, 2, 1, -1), (3, 7, 3, 5),
+                                                     (8, 64, 1, 40), (2, 1, 1, 1)])
+def test_partition_bit_exact_against_oracle(parts, ps, dist, short_max):
+    rng = np.random.default_rng(parts * 100 + ps)
+    row_ptr, col = inputs.rmat_graph(12, 50000, 0.57, 0.19, 0.19, 0.05, rng)
+    n = row_ptr.size - 1
+    bounds = inputs.equal_node_bounds(n, parts)
+    for p in range(parts):
+        _compare_with_oracle(row_ptr, col, parts, p, bounds, ps=ps, dist=dist, short_max=short_max)
+
+
+def test_partition_with_self_loops_duplicates_and_empty_ranges():
+    row_ptr, col = inputs.csr_from_adjacency_lists([[0, 1, 1, 3], [0], [], [0, 3, 3]])
+    bounds = [0, 2, 2, 4]                     # the middle range is empty
+    for p in range(3):
+        got, info = _compare_with_oracle(row_ptr, col, 3, p, np.array(bounds), ps=2, dist=1, short_max=-1)
+    assert info.n_own == 2
+    empty = binding.mgg_build_partition(np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32), host_only=True)
+    assert empty.info.n_own == 0 and empty.info.n_items == 0
+
+
+def test_default_bounds_are_the_equal_node_split():
+    rng = np.random.default_rng(5)
+    row_ptr, col = inputs.rmat_graph(10, 5000, 0.45, 0.22, 0.22, 0.11, rng, n_nodes=1000)
+    for parts in (1, 3, 7):
+        b = inputs.equal_node_bounds(1000, parts)
+        for p in range(parts):
+            part = binding.mgg_build_partition(row_ptr, col, parts, p, None, host_only=True)
+            assert (part.info.lb, part.info.ub) == (b[p], b[p + 1])
+
+
+def test_scaled_configs_bit_exact():
+    for cfg, shrink in ((2, 6), (3, 8), (5, 7)):
+        w = inputs.config(cfg, shrink=shrink)
+        _compare_with_oracle(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
+
+
+def test_edge_balanced_split_matches_oracle():
+    rng = np.random.default_rng(9)
+    row_ptr, _ = inputs.rmat_graph(13, 100000, 0.57, 0.19, 0.19, 0.05, rng)
+    for parts in (1, 2, 4, 8, 16, 31):
+        assert np.array_equal(binding.mgg_split_edge_balanced(row_ptr, parts),
+                              oracle.split_edge_balanced(row_ptr, parts))
+
+
+def _status(fn, *a, **k):
+    with pytest.raises(MggError) as e:
+        fn(*a, **k)
+    return e.value.status
+
+
+def test_bad_arguments_are_error_codes_not_crashes():
+    rp = np.array([0, 1, 2], dtype=np.int64)
+    col = np.array([1, 0], dtype=np.int32)
+    ho = dict(host_only=True)
+    assert _status(binding.mgg_build_partition, np.array([0, 2, 1]), col, **ho) == binding.ERR_BAD_GRAPH
+    assert _status(binding.mgg_build_partition, np.array([1, 1, 2]), col, **ho) == binding.ERR_BAD_GRAPH
+    assert _status(binding.mgg_build_partition, rp, np.array([1, 2], dtype=np.int32), **ho) == binding.ERR_BAD_GRAPH
+    assert _status(binding.mgg_build_partition, rp, np.array([-1, 0], dtype=np.int32), **ho) == binding.ERR_BAD_GRAPH
+    assert _status(binding.mgg_build_partition, rp, col, 2, 2, **ho) == binding.ERR_INVALID_ARG
+    assert _status(binding.mgg_build_partition, rp, col, 2, -1, **ho) == binding.ERR_INVALID_ARG
+    assert _status(binding.mgg_build_partition, rp, col, 0, 0, **ho) == binding.ERR_INVALID_ARG
+    assert _status(binding.mgg_build_partition, rp, col, 2, 0, [0, 3, 2], **ho) == binding.ERR_INVALID_ARG
+    assert _status(binding.mgg_build_partition, rp, col, 2, 0, [0, 1, 3], **ho) == binding.ERR_INVALID_ARG
+    assert _status(binding.mgg_build_partition, rp, col, ps=65, **ho) == binding.ERR_INVALID_ARG
+    assert _status(binding.mgg_build_partition, rp, col, dist=-3, **ho) == binding.ERR_INVALID_ARG
+    assert _status(binding.mgg_set_option, "no_such_option", 1) == binding.ERR_INVALID_ARG
+    assert _status(binding.mgg_set_option, "lds_halo", 7) == binding.ERR_INVALID_ARG
+    lib = binding.lib()
+    assert lib.mgg_build_partition(2, None, None, 1, 0, None, None, None) == binding.ERR_INVALID_ARG
+    h = ctypes.c_void_p()
+    assert lib.mgg_build_partition(2, None, None, 1, 0, None, None, ctypes.byref(h)) == binding.ERR_INVALID_ARG
+    assert h.value is None and b"NULL" in lib.mgg_last_error()
+    lib.mgg_partition_destroy(None)
+
+
+def test_device_calls_refuse_a_host_only_partition():
+    part = binding.mgg_build_partition(np.array([0, 1, 2]), np.array([1, 0], dtype=np.int32), host_only=True)
+    lib = binding.lib()
+    st = lib.mgg_aggregate(part.handle, 0, 0.0, 0, ctypes.c_void_p(256), None, 4, 4, ctypes.c_void_p(512), 4, None)
+    assert st == binding.ERR_INVALID_ARG and b"host-only" in lib.mgg_last_error()
+    assert lib.mgg_update(4, 0, None, 4, 4, 0, None, None, 4, 0, 0, None, 4, None) == binding.ERR_INVALID_ARG
+    assert lib.mgg_update(4, 1, ctypes.c_void_p(256), 4, 4, 0, ctypes.c_void_p(256), None, 4, 0, 0,
+                          ctypes.c_void_p(512), 4, None) == binding.ERR_UNSUPPORTED
+
+
+def test_options_round_trip():
+    for key in ("xcd_remap", "lds_halo"):
+        old = binding.mgg_get_option(key)
+        binding.mgg_set_option(key, 1 - old)
+        assert binding.mgg_get_option(key) == 1 - old
+        binding.mgg_set_option(key, old)
