@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the GNN-layer hot path (aggregation + Update) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--verify]
+
+A step is one forward pass of every layer of the chosen workload (default: config 2, the
+R-MAT 2^20 share with halo table) with all inputs already resident in HBM.  The timed region
+holds exactly K steps between two device synchronisations.  One JSON line is printed:
+whole-step throughput in GEdges/s, the roofline figures of the dominant kernel (the
+aggregation kernel, bound by HBM bandwidth) from HIP events recorded on the launch stream
+inside the timed region, and the CPU oracle timed on the host cores as a baseline.
+
+One GPU only: collectives and sharding are not part of this build.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+# HBM bytes per aggregation launch from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), scaled by
+# the factor the same counters read for a plain copy kernel; see profiles/ for the summaries.
+# workload name -> bytes per launch of the dominant aggregation kernel (None = not measured)
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def to_dev(a, dev):
+    import torch
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16).copy()).to(dev).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+def gather_model_bytes(nnz, n_own, dim, elem_bytes, gcn):
+    """Algorithmic bytes of one aggregation launch: per neighbour one embedding row, its 4-byte
+    id and (GCN) the 4-byte normalisation factor of the neighbour; per owned row its own
+    embedding, the fp32 output row, two row-pointer entries and its normalisation factor."""
+    per_edge = dim * elem_bytes + 4 + (4 if gcn else 0)
+    per_row = dim * elem_bytes + dim * 4 + 12
+    return nnz * per_edge + n_own * per_row
+
+
+def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 20.0):
+    import torch
+    from paper_2209_06800_amd import binding, inputs
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    t0 = time.time()
+    w = inputs.config(cfg)
+    log(f"[bench] generated {w.name}: {inputs.graph_stats(w.row_ptr)} in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    part = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
+    info = part.info
+    halo_gid = part.export()["halo_gid"]
+    nnz = int(info.nnz_local + info.nnz_remote)
+    log(f"[bench] partition {w.part_id}/{w.parts}: n_own={info.n_own} nnz_local={info.nnz_local} "
+        f"nnz_remote={info.nnz_remote} halo={info.num_halo} items={info.n_items} split_rows={info.n_split_rows} "
+        f"short_rows={info.n_short_rows} in {time.time() - t0:.1f}s")
+
+    bf16 = w.dtype == "bf16"
+    esz = 2 if bf16 else 4
+    x_local_np, x_halo_np = w.x[w.lb:w.ub], w.x[halo_gid]
+    # per layer: device inputs, weights, buffers
+    layers = []
+    for li, layer in enumerate(w.layers):
+        d_in = layer.dims[0]
+        if li == 0:
+            xl, xh = to_dev(x_local_np, dev), (to_dev(x_halo_np, dev) if halo_gid.size else None)
+            lesz = esz
+        else:
+            # layer 2 reads layer 1's output for owned rows; halo rows are a seeded stand-in for
+            # what the other partitions would have produced
+            xl = layers[li - 1]["out"]
+            xh = to_dev(inputs.layer2_halo_table(w.notes["layer2_halo_seed"], int(info.num_halo), d_in), dev)
+            lesz = 4
+        ws = [to_dev(m, dev) for m in layer.weights]
+        agg = torch.empty((int(info.n_own), d_in), dtype=torch.float32, device=dev)
+        hid = None
+        if len(ws) == 2:
+            hid = torch.empty((int(info.n_own), layer.dims[1]), dtype=torch.bfloat16 if bf16 else torch.float32, device=dev)
+        out = torch.empty((int(info.n_own), layer.dims[-1]), dtype=torch.float32, device=dev)
+        layers.append(dict(layer=layer, xl=xl, xh=xh, ws=ws, agg=agg, hid=hid, out=out, esz=lesz,
+                           bytes=gather_model_bytes(nnz, int(info.n_own), d_in, lesz, layer.mode == "gcn"),
+                           flops=sum(2.0 * info.n_own * layer.dims[i] * layer.dims[i + 1] for i in range(len(ws)))))
+
+    def step(events=None):
+        for li, L in enumerate(layers):
+            layer = L["layer"]
+            if events is not None:
+                events[li][0].record()
+            binding.mgg_aggregate(part, layer.mode, L["xl"], L["xh"], eps=layer.eps, out=L["agg"])
+            if events is not None:
+                events[li][1].record()
+            if len(L["ws"]) == 1:
+                binding.mgg_update(L["agg"], L["ws"][0], None, layer.acts[0], out=L["out"])
+            else:
+                binding.mgg_update(L["agg"], L["ws"][0], None, layer.acts[0], out=L["hid"])
+                binding.mgg_update(L["hid"], L["ws"][1], None, layer.acts[1], out=L["out"])
+            if events is not None:
+                events[li][2].record()
+
+    for _ in range(max(warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+
+    ev = [[[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in layers] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(steps):
+        step(ev[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed * 1e3 / steps
+
+    agg_ms = [float(np.mean([ev[k][li][0].elapsed_time(ev[k][li][1]) for k in range(steps)])) for li in range(len(layers))]
+    upd_ms = [float(np.mean([ev[k][li][1].elapsed_time(ev[k][li][2]) for k in range(steps)])) for li in range(len(layers))]
+    dom = int(np.argmax([L["bytes"] for L in layers]))
+    achieved = layers[dom]["bytes"] / (agg_ms[dom] * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
+
+    per_layer = []
+    for li, L in enumerate(layers):
+        per_layer.append({
+            "layer": li, "agg_dim": L["layer"].dims[0], "agg_ms": round(agg_ms[li], 4),
+            "agg_gedges_per_s": round(nnz / (agg_ms[li] * 1e-3) / 1e9, 3),
+            "agg_model_gbs": round(L["bytes"] / (agg_ms[li] * 1e-3) / 1e9, 1),
+            "agg_frac_of_hbm_peak": round(L["bytes"] / (agg_ms[li] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "update_ms": round(upd_ms[li], 4),
+            "update_tflops": round(L["flops"] / (upd_ms[li] * 1e-3) / 1e12, 2),
+        })
+
+    if verify:
+        import oracle
+        rng = np.random.default_rng(0)
+        deg = np.diff(w.row_ptr)[w.lb:w.ub]
+        rows = np.unique(np.concatenate([np.argsort(deg)[-4:], rng.integers(0, int(info.n_own), 200)]))
+        L0 = layers[0]
+        ref = oracle.aggregate(w.row_ptr, w.col, L0["layer"].mode, x_local_np, lb=w.lb, ub=w.ub, x_halo=x_halo_np,
+                               halo_gid=halo_gid, eps=L0["layer"].eps, rows=rows)
+        got = L0["agg"][torch.from_numpy(rows).to(dev)].cpu().numpy().astype(np.float64)
+        err = np.abs(got - ref)
+        log(f"[bench] verify layer-0 aggregation on {rows.size} sampled rows: max abs err {err.max():.3e}, "
+            f"max err / (1e-6 + 1e-4|ref|) = {(err / (1e-6 + 1e-4 * np.abs(ref))).max():.3f}")
+
+    # ---- CPU baseline: the oracle as it stands, on the host cores, on a bounded sample ------------
+    import oracle
+    L0 = layers[0]
+    n_own = int(info.n_own)
+    deg_share = (np.diff(w.row_ptr)[w.lb:w.ub]).astype(np.int64)
+    # pick a contiguous-in-row-order sample whose work fits the budget (oracle ~ a few GFMA/s/core-set)
+    work = deg_share * w.dim
+    budget = cpu_budget_s * 0.6e9 * max(1, oracle.num_threads()) / 8.0
+    rows = np.arange(n_own)
+    if work.sum() > budget:
+        rng = np.random.default_rng(1)
+        perm = rng.permutation(n_own)
+        take = int(np.searchsorted(np.cumsum(work[perm]), budget)) + 1
+        rows = np.sort(perm[:take])
+    sample_edges = int(deg_share[rows].sum())
+    t0 = time.perf_counter()
+    h = oracle.aggregate(w.row_ptr, w.col, L0["layer"].mode, x_local_np, lb=w.lb, ub=w.ub, x_halo=x_halo_np,
+                         halo_gid=halo_gid, eps=L0["layer"].eps, rows=rows)
+    for i, m in enumerate(L0["layer"].weights):
+        h = oracle.update(h, m, None, L0["layer"].acts[i])
+    cpu_s = time.perf_counter() - t0
+    cpu_baseline = {"value": round(sample_edges / cpu_s / 1e9, 5), "unit": "GEdges/s", "cores": oracle.num_threads(),
+                    "kind": "oracle",
+                    "sample": f"layer 0 (aggregate + update) on {rows.size} of {n_own} owned rows, "
+                              f"{sample_edges} edges, {cpu_s:.1f}s"}
+
+    result = {
+        "metric": "aggregation GEdges/s and achieved HBM GB/s (% of peak) per layer, 1 MI355X",
+        "value": round(nnz * len(layers) / (ms_per_step * 1e-3) / 1e9, 4),
+        "unit": "GEdges/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 in, f32 accumulate" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "share": f"{w.part_id}/{w.parts}", "n_own": n_own, "nnz_local": int(info.nnz_local),
+                   "nnz_remote": int(info.nnz_remote), "num_halo": int(info.num_halo),
+                   "layers": [L["layer"].dims for L in layers], "ps": int(info.ps), "dist": int(info.dist),
+                   "short_max": int(info.short_max)},
+        "roofline": {"bound": "hbm", "kernel": f"aggregate (layer {dom}, dim {layers[dom]['layer'].dims[0]})",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": traffic, "algorithmic_bytes": int(layers[dom]["bytes"]),
+                     "kernel_ms": round(agg_ms[dom], 4)},
+        "cpu_baseline": cpu_baseline,
+        "per_layer": per_layer,
+    }
+    part.destroy()
+    return result
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--verify", action="store_true", help="compare sampled rows with the CPU oracle")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU's share on one MI355X; multi-GPU runs are not part of this build "
+              "(no collectives, no second GPU). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    res = run(args.config, args.steps, args.warmup, args.verify, args.cpu_seconds)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -76,6 +76,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2209_06800_amd.build` "
                               "(there is no fallback path)")
+        # torch first: it ships its own HIP runtime under the same soname, and the stream
+        # handles and device pointers handed to the library must belong to that runtime
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.mgg_last_error.restype = C.c_char_p
         L.mgg_version.restype = C.c_char_p
