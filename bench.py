@@ -31,7 +31,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # HBM bytes per aggregation launch from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), scaled by
 # the factor the same counters read for a plain copy kernel; see profiles/ for the summaries.
 # workload name -> bytes per launch of the dominant aggregation kernel (None = not measured)
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    "cfg2_rmat20_gcn64_p4": 3643682077,   # profiles/aggregate_cfg2_rmat20_gcn64_first_kernel.md
+}
 
 
 def log(*a):
@@ -54,7 +56,33 @@ def gather_model_bytes(nnz, n_own, dim, elem_bytes, gcn):
     return nnz * per_edge + n_own * per_row
 
 
-def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 20.0):
+def cpu_baseline_leg(w, layer, x_local_np, x_halo_np, halo_gid, n_own, cpu_budget_s):
+    """The oracle as it stands (never tuned for this), timed on the host cores on a bounded
+    sample of the same workload: layer 0, aggregate + update, on a random subset of owned rows."""
+    import oracle
+    deg_share = (np.diff(w.row_ptr)[w.lb:w.ub]).astype(np.int64)
+    work = deg_share * w.dim
+    budget = cpu_budget_s * 0.6e9 * max(1, oracle.num_threads()) / 8.0
+    rows = np.arange(n_own)
+    if work.sum() > budget:
+        rng = np.random.default_rng(1)
+        perm = rng.permutation(n_own)
+        take = int(np.searchsorted(np.cumsum(work[perm]), budget)) + 1
+        rows = np.sort(perm[:take])
+    sample_edges = int(deg_share[rows].sum())
+    t0 = time.perf_counter()
+    h = oracle.aggregate(w.row_ptr, w.col, layer.mode, x_local_np, lb=w.lb, ub=w.ub, x_halo=x_halo_np,
+                         halo_gid=halo_gid, eps=layer.eps, rows=rows)
+    for i, m in enumerate(layer.weights):
+        h = oracle.update(h, m, None, layer.acts[i])
+    cpu_s = time.perf_counter() - t0
+    return {"value": round(sample_edges / cpu_s / 1e9, 5), "unit": "GEdges/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"layer 0 (aggregate + update) on {rows.size} of {n_own} owned rows, "
+                      f"{sample_edges} edges, {cpu_s:.1f}s"}
+
+
+def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 20.0, calibrate_copy: bool = False):
     import torch
     from paper_2209_06800_amd import binding, inputs
 
@@ -114,6 +142,16 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
             if events is not None:
                 events[li][2].record()
 
+    if calibrate_copy:
+        # a plain device-to-device copy of known size, so that a counter run (rocprofv3 --pmc
+        # FETCH_SIZE / WRITE_SIZE) can be scaled: each launch reads 1 GiB and writes 1 GiB
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)       # an elementwise kernel, not a DMA copy
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(max(warmup, 1)):
         step()
     torch.cuda.synchronize()
@@ -157,32 +195,11 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
         log(f"[bench] verify layer-0 aggregation on {rows.size} sampled rows: max abs err {err.max():.3e}, "
             f"max err / (1e-6 + 1e-4|ref|) = {(err / (1e-6 + 1e-4 * np.abs(ref))).max():.3f}")
 
-    # ---- CPU baseline: the oracle as it stands, on the host cores, on a bounded sample ------------
-    import oracle
-    L0 = layers[0]
+    cpu_baseline = None
+    if cpu_budget_s > 0:
+        cpu_baseline = cpu_baseline_leg(w, layers[0]["layer"], x_local_np, x_halo_np, halo_gid, int(info.n_own),
+                                        cpu_budget_s)
     n_own = int(info.n_own)
-    deg_share = (np.diff(w.row_ptr)[w.lb:w.ub]).astype(np.int64)
-    # pick a contiguous-in-row-order sample whose work fits the budget (oracle ~ a few GFMA/s/core-set)
-    work = deg_share * w.dim
-    budget = cpu_budget_s * 0.6e9 * max(1, oracle.num_threads()) / 8.0
-    rows = np.arange(n_own)
-    if work.sum() > budget:
-        rng = np.random.default_rng(1)
-        perm = rng.permutation(n_own)
-        take = int(np.searchsorted(np.cumsum(work[perm]), budget)) + 1
-        rows = np.sort(perm[:take])
-    sample_edges = int(deg_share[rows].sum())
-    t0 = time.perf_counter()
-    h = oracle.aggregate(w.row_ptr, w.col, L0["layer"].mode, x_local_np, lb=w.lb, ub=w.ub, x_halo=x_halo_np,
-                         halo_gid=halo_gid, eps=L0["layer"].eps, rows=rows)
-    for i, m in enumerate(L0["layer"].weights):
-        h = oracle.update(h, m, None, L0["layer"].acts[i])
-    cpu_s = time.perf_counter() - t0
-    cpu_baseline = {"value": round(sample_edges / cpu_s / 1e9, 5), "unit": "GEdges/s", "cores": oracle.num_threads(),
-                    "kind": "oracle",
-                    "sample": f"layer 0 (aggregate + update) on {rows.size} of {n_own} owned rows, "
-                              f"{sample_edges} edges, {cpu_s:.1f}s"}
-
     result = {
         "metric": "aggregation GEdges/s and achieved HBM GB/s (% of peak) per layer, 1 MI355X",
         "value": round(nnz * len(layers) / (ms_per_step * 1e-3) / 1e9, 4),
@@ -213,13 +230,15 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--verify", action="store_true", help="compare sampled rows with the CPU oracle")
-    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the cpu_baseline leg")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the cpu_baseline leg (0 = skip it)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a 1 GiB device copy three times (reference for rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU's share on one MI355X; multi-GPU runs are not part of this build "
               "(no collectives, no second GPU). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
-    res = run(args.config, args.steps, args.warmup, args.verify, args.cpu_seconds)
+    res = run(args.config, args.steps, args.warmup, args.verify, args.cpu_seconds, args.calibrate_copy)
     print(json.dumps(res), flush=True)
 
 

@@ -121,12 +121,14 @@ def chung_lu_pareto(n: int, alpha: float, d_min: float, d_max: float,
                     rng: np.random.Generator, chunk: int = 1 << 24):
     """Chung-Lu graph on truncated-Pareto expected degrees, node ids in random order.
 
-    w_v ~ Pareto(alpha) truncated to [d_min, d_max] (inverse-CDF sampling);
+    The density of w_v falls as w^-alpha (a Zipf-like degree law with exponent alpha), i.e.
+    the tail P(w > t) falls as t^-(alpha-1); truncated to [d_min, d_max], inverse-CDF sampling.
     m = sum(w)/2 endpoint pairs are drawn with probability proportional to w.
     """
     u = rng.random(n)
-    lo, hi = d_min ** (-alpha), d_max ** (-alpha)
-    w = (lo - u * (lo - hi)) ** (-1.0 / alpha)
+    a = alpha - 1.0
+    lo, hi = d_min ** (-a), d_max ** (-a)
+    w = (lo - u * (lo - hi)) ** (-1.0 / a)
     m = int(w.sum() / 2)
     cdf = np.cumsum(w)
     cdf /= cdf[-1]
@@ -253,7 +255,7 @@ def config(cfg: int, shrink: int = 0) -> Workload:
     if cfg == 4:
         n = 232965 >> shrink
         # expected degrees keep the paper-scale floor; the cap follows the node count
-        row_ptr, col = chung_lu_pareto(n, 2.1, 113.0, float(min(20000, n // 8)), rng)
+        row_ptr, col = chung_lu_pareto(n, 2.1, 115.5, float(min(20000, n // 8)), rng)
         x = normal_f32((n, 602), rng)
         layers = [Layer("gcn", 0.0, [_weights(602, 256, rng, "f32")], ["relu"], [602, 256])]
         return Workload("cfg4_powerlaw233k_gcn602", 4, n, row_ptr, col, 1, 0,
