@@ -241,9 +241,65 @@ __device__ __forceinline__ void accumulate_list(Acc<K> &acc, const typename K::e
     }
 }
 
+// ---- optional LDS staging of halo rows (section 5.2, "pipelined memory operation") -----------
+// The rows of a remote partition are requested with global_load_lds: the data go from memory
+// straight into this wavefront's LDS stage, holding no registers while in flight.  The local
+// partition of the same pair is then accumulated through registers, and only afterwards does
+// the wavefront wait for the staged rows and add them.  One stage holds kStageInstr load
+// instructions (1 KB each: 64/LPR rows).  Only for 16-byte vectors and one chunk per lane.
+constexpr int kStageInstr = 8;
+
 template <class K>
+__device__ __forceinline__ void stage_halo_rows(uint4 (*stage)[kWave], const typename K::elem *table, int64_t ld,
+                                                int my_idx, int len, int t0, int sub, int lis, int nvec)
+{
+#pragma unroll
+    for (int u = 0; u < kStageInstr; ++u) {
+        if ((t0 + u) * K::NPW >= len) break;                     // wave-uniform
+        const int j = (t0 + u) * K::NPW + sub;
+        const int idx = __shfl(my_idx, j & 63);
+        const bool ok = j < len && lis < nvec;
+        // lanes with nothing to fetch read the first bytes of the table (always valid memory)
+        const typename K::elem *src = ok ? table + static_cast<int64_t>(idx) * ld + static_cast<int64_t>(lis) * K::VEC : table;
+        typedef const __attribute__((address_space(1))) void *gptr_t;
+        typedef __attribute__((address_space(3))) void *lptr_t;
+        __builtin_amdgcn_global_load_lds((gptr_t)(const void *)src, (lptr_t)(void *)&stage[u][0], 16, 0, 0);
+    }
+}
+
+template <class K>
+__device__ __forceinline__ void consume_staged_rows(Acc<K> &acc, uint4 (*stage)[kWave], const typename K::elem *table,
+                                                    int64_t ld, int my_idx, float my_w, int len, int sub, int lis,
+                                                    int nvec, int lane)
+{
+    const int steps = (len + K::NPW - 1) / K::NPW;
+    for (int t0 = 0; t0 < steps; t0 += kStageInstr) {
+        if (t0 > 0) stage_halo_rows<K>(stage, table, ld, my_idx, len, t0, sub, lis, nvec);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // staged rows have landed in LDS
+#pragma unroll
+        for (int u = 0; u < kStageInstr; ++u) {
+            if ((t0 + u) * K::NPW >= len) break;
+            const int j = (t0 + u) * K::NPW + sub;
+            const float wj = __shfl(my_w, j & 63);
+            const bool ok = j < len && lis < nvec;
+            uint4 q = stage[u][lane];
+            if (!ok) q = make_uint4(0u, 0u, 0u, 0u);
+            typename K::raw r;
+            __builtin_memcpy(&r, &q, sizeof r);
+            float f[K::VEC];
+            unpack<K::BF16, K::VEC>(r, f);
+            const float w = ok ? wj : 0.f;
+#pragma unroll
+            for (int e = 0; e < K::VEC; ++e) acc.v[0][e] = fmaf(w, f[e], acc.v[0][e]);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // stage is free for the next batch
+    }
+}
+
+template <class K, bool LDSH>
 __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
 {
+    __shared__ uint4 stage_all[LDSH ? kWavesPerBlock : 1][LDSH ? kStageInstr : 1][LDSH ? kWave : 1];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int sub = lane / K::LPR;      // which neighbour row of a load instruction
@@ -273,8 +329,15 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
             load_partition_ids(a.local_col, a.dinv_own, it.lbeg + off, min(ps, n_l - off), lane, gcn, nidx_l, nw_l);
             load_partition_ids(a.remote_col, a.dinv_halo, it.rbeg + off, min(ps, n_r - off), lane, gcn, nidx_r, nw_r);
             const int len_l = min(ps, n_l - g * ps), len_r = min(ps, n_r - g * ps);
-            if (len_l > 0) accumulate_partition<K>(acc, xl, a.ld_x, idx_l, w_l, len_l, sub, lis, a.nvec);
-            if (len_r > 0) accumulate_partition<K>(acc, xh, a.ld_x, idx_r, w_r, len_r, sub, lis, a.nvec);
+            if constexpr (LDSH) {
+                uint4 (*stage)[kWave] = stage_all[wave];
+                if (len_r > 0) stage_halo_rows<K>(stage, xh, a.ld_x, idx_r, len_r, 0, sub, lis, a.nvec);
+                if (len_l > 0) accumulate_partition<K>(acc, xl, a.ld_x, idx_l, w_l, len_l, sub, lis, a.nvec);
+                if (len_r > 0) consume_staged_rows<K>(acc, stage, xh, a.ld_x, idx_r, w_r, len_r, sub, lis, a.nvec, lane);
+            } else {
+                if (len_l > 0) accumulate_partition<K>(acc, xl, a.ld_x, idx_l, w_l, len_l, sub, lis, a.nvec);
+                if (len_r > 0) accumulate_partition<K>(acc, xh, a.ld_x, idx_r, w_r, len_r, sub, lis, a.nvec);
+            }
             idx_l = nidx_l; w_l = nw_l; idx_r = nidx_r; w_r = nw_r;
         }
         // combine the sub-wave accumulators: lanes with equal `lis` hold the same columns
@@ -302,49 +365,75 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
     }
 }
 
-// Rows cut into several items: add the partial sums in slot order, then finish the row.
+// Rows cut into several items: one workgroup per such row adds its partial sums in a fixed
+// order (wave w takes slots w, w+4, ... front to back; the four wave sums are then added
+// 0+1+2+3), adds the self term and the row factor, and writes the row.  64 columns at a time.
 template <bool BF16>
-__global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_rows, int32_t n_split, int32_t dim,
-                                                       const float *scratch, int64_t scratch_ld, const void *x_local,
-                                                       int64_t ld_x, const float *dinv_own, int32_t gcn, float self_w,
-                                                       float *out, int64_t ld_out)
+__global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_rows, int32_t dim, const float *scratch,
+                                                       int64_t scratch_ld, const void *x_local, int64_t ld_x,
+                                                       const float *dinv_own, int32_t gcn, float self_w, float *out,
+                                                       int64_t ld_out)
 {
-    const int64_t tid = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    const int64_t total = static_cast<int64_t>(n_split) * dim;
-    if (tid >= total) return;
-    const int32_t s = static_cast<int32_t>(tid / dim), k = static_cast<int32_t>(tid % dim);
-    const SplitRow sr = split_rows[s];
-    float sum = 0.f;
-    for (int32_t i = 0; i < sr.n_slots; ++i) sum += scratch[static_cast<int64_t>(sr.first_slot + i) * scratch_ld + k];
-    float xv;
-    if constexpr (BF16)
-        xv = __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k]) << 16);
-    else
-        xv = static_cast<const float *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k];
+    __shared__ float part[kWavesPerBlock][kWave];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const SplitRow sr = split_rows[blockIdx.x];
     const float dv = gcn ? dinv_own[sr.row] : 1.f;
     const float ws = gcn ? dv : self_w;
-    out[static_cast<int64_t>(sr.row) * ld_out + k] = dv * (sum + ws * xv);
+    for (int k0 = 0; k0 < dim; k0 += kWave) {
+        const int k = k0 + lane;
+        float sum = 0.f;
+        if (k < dim) {
+            const float *src = scratch + static_cast<int64_t>(sr.first_slot) * scratch_ld + k;
+            int i = wave;
+            for (; i + 3 * kWavesPerBlock < sr.n_slots; i += 4 * kWavesPerBlock) {
+                const float v0 = src[static_cast<int64_t>(i) * scratch_ld];
+                const float v1 = src[static_cast<int64_t>(i + kWavesPerBlock) * scratch_ld];
+                const float v2 = src[static_cast<int64_t>(i + 2 * kWavesPerBlock) * scratch_ld];
+                const float v3 = src[static_cast<int64_t>(i + 3 * kWavesPerBlock) * scratch_ld];
+                sum = (((sum + v0) + v1) + v2) + v3;
+            }
+            for (; i < sr.n_slots; i += kWavesPerBlock) sum += src[static_cast<int64_t>(i) * scratch_ld];
+        }
+        part[wave][lane] = sum;
+        __syncthreads();
+        if (wave == 0 && k < dim) {
+            const float total = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
+            float xv;
+            if constexpr (BF16)
+                xv = __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k]) << 16);
+            else
+                xv = static_cast<const float *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k];
+            out[static_cast<int64_t>(sr.row) * ld_out + k] = dv * (total + ws * xv);
+        }
+        __syncthreads();
+    }
 }
 
 template <class K>
-hipError_t launch_cfg(const AggArgs &a, int grid, hipStream_t stream)
+hipError_t launch_cfg(const AggArgs &a, int grid, hipStream_t stream, bool lds_halo)
 {
-    hipLaunchKernelGGL(aggregate_kernel<K>, dim3(grid), dim3(kBlock), 0, stream, a);
+    if constexpr (K::CH == 1 && sizeof(typename K::raw) == 16) {
+        if (lds_halo) {
+            hipLaunchKernelGGL((aggregate_kernel<K, true>), dim3(grid), dim3(kBlock), 0, stream, a);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((aggregate_kernel<K, false>), dim3(grid), dim3(kBlock), 0, stream, a);
     return hipGetLastError();
 }
 
 // LPR = smallest power of two >= nvec (at least 4, at most 64); CH = chunks per lane.
 template <bool BF16, int VEC>
-hipError_t dispatch_shape(const AggArgs &a, int grid, hipStream_t stream, int lpr, int ch)
+hipError_t dispatch_shape(const AggArgs &a, int grid, hipStream_t stream, int lpr, int ch, bool lds)
 {
-    if (lpr == 4) return launch_cfg<Cfg<BF16, VEC, 4, 1>>(a, grid, stream);
-    if (lpr == 8) return launch_cfg<Cfg<BF16, VEC, 8, 1>>(a, grid, stream);
-    if (lpr == 16) return launch_cfg<Cfg<BF16, VEC, 16, 1>>(a, grid, stream);
-    if (lpr == 32) return launch_cfg<Cfg<BF16, VEC, 32, 1>>(a, grid, stream);
-    if (ch == 1) return launch_cfg<Cfg<BF16, VEC, 64, 1>>(a, grid, stream);
-    if (ch == 2) return launch_cfg<Cfg<BF16, VEC, 64, 2>>(a, grid, stream);
-    if (ch <= 4) return launch_cfg<Cfg<BF16, VEC, 64, 4>>(a, grid, stream);
-    return launch_cfg<Cfg<BF16, VEC, 64, 8>>(a, grid, stream);
+    if (lpr == 4) return launch_cfg<Cfg<BF16, VEC, 4, 1>>(a, grid, stream, lds);
+    if (lpr == 8) return launch_cfg<Cfg<BF16, VEC, 8, 1>>(a, grid, stream, lds);
+    if (lpr == 16) return launch_cfg<Cfg<BF16, VEC, 16, 1>>(a, grid, stream, lds);
+    if (lpr == 32) return launch_cfg<Cfg<BF16, VEC, 32, 1>>(a, grid, stream, lds);
+    if (ch == 1) return launch_cfg<Cfg<BF16, VEC, 64, 1>>(a, grid, stream, lds);
+    if (ch == 2) return launch_cfg<Cfg<BF16, VEC, 64, 2>>(a, grid, stream, lds);
+    if (ch <= 4) return launch_cfg<Cfg<BF16, VEC, 64, 4>>(a, grid, stream, lds);
+    return launch_cfg<Cfg<BF16, VEC, 64, 8>>(a, grid, stream, lds);
 }
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -406,28 +495,27 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
     const int npw = 64 / lpr;
     const int short_waves = (a.n_short + npw - 1) / npw;
     const int grid = a.n_item_blocks + (short_waves + kWavesPerBlock - 1) / kWavesPerBlock;
+    const bool lds = option_lds_halo() != 0 && !p->halo_gid.empty();
     if (grid > 0) {
         hipError_t e;
         if (bf16) {
-            if (vec == 8) e = dispatch_shape<true, 8>(a, grid, stream, lpr, ch);
-            else if (vec == 2) e = dispatch_shape<true, 2>(a, grid, stream, lpr, ch);
-            else e = dispatch_shape<true, 1>(a, grid, stream, lpr, ch);
+            if (vec == 8) e = dispatch_shape<true, 8>(a, grid, stream, lpr, ch, lds);
+            else if (vec == 2) e = dispatch_shape<true, 2>(a, grid, stream, lpr, ch, lds);
+            else e = dispatch_shape<true, 1>(a, grid, stream, lpr, ch, lds);
         } else {
-            if (vec == 4) e = dispatch_shape<false, 4>(a, grid, stream, lpr, ch);
-            else if (vec == 2) e = dispatch_shape<false, 2>(a, grid, stream, lpr, ch);
-            else e = dispatch_shape<false, 1>(a, grid, stream, lpr, ch);
+            if (vec == 4) e = dispatch_shape<false, 4>(a, grid, stream, lpr, ch, lds);
+            else if (vec == 2) e = dispatch_shape<false, 2>(a, grid, stream, lpr, ch, lds);
+            else e = dispatch_shape<false, 1>(a, grid, stream, lpr, ch, lds);
         }
         if (e != hipSuccess) return hip_fail(e, "aggregate kernel launch");
     }
     const int32_t n_split = static_cast<int32_t>(p->split_rows.size());
     if (n_split > 0) {
-        const int64_t total = static_cast<int64_t>(n_split) * dim;
-        const int fgrid = static_cast<int>((total + kBlock - 1) / kBlock);
         if (bf16)
-            hipLaunchKernelGGL(fixup_kernel<true>, dim3(fgrid), dim3(kBlock), 0, stream, p->d.split_rows, n_split, dim,
+            hipLaunchKernelGGL(fixup_kernel<true>, dim3(n_split), dim3(kBlock), 0, stream, p->d.split_rows, dim,
                                p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out);
         else
-            hipLaunchKernelGGL(fixup_kernel<false>, dim3(fgrid), dim3(kBlock), 0, stream, p->d.split_rows, n_split, dim,
+            hipLaunchKernelGGL(fixup_kernel<false>, dim3(n_split), dim3(kBlock), 0, stream, p->d.split_rows, dim,
                                p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "fix-up kernel launch");

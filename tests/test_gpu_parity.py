@@ -204,6 +204,28 @@ def test_results_do_not_depend_on_scheduling():
         assert torch.equal(a, b)
 
 
+@pytest.fixture
+def lds_halo():
+    binding.mgg_set_option("lds_halo", 1)
+    yield
+    binding.mgg_set_option("lds_halo", 0)
+
+
+@pytest.mark.parametrize("dim,bf16", [(16, False), (64, False), (100, False), (256, False), (128, True), (8, True), (512, True)])
+@pytest.mark.parametrize("build", [dict(), dict(ps=7, dist=2), dict(ps=64, dist=4), dict(ps=1, dist=40, short_max=-1)])
+def test_lds_staged_halo_rows_give_the_same_answer(lds_halo, dim, bf16, build):
+    """Halo rows staged through LDS ahead of their accumulation (section 5.2) change the
+    schedule only; shapes the staged path does not cover fall back to register loads."""
+    row_ptr, col, rng = small_rmat(seed=300 + dim)
+    n = row_ptr.size - 1
+    x = rng.standard_normal((n, dim)).astype(np.float32)
+    if bf16:
+        x = inputs.to_bf16_bits(x)
+    bounds = inputs.equal_node_bounds(n, 4)
+    for p, mode in ((0, "gcn"), (3, "gin")):
+        check_aggregate(row_ptr, col, 4, p, bounds, x, mode, build=build, what=f"lds dim {dim} {build} part {p}")
+
+
 # ----------------------------------------------------------------------------- update
 def update_bound(a64, w64, k, bf16):
     s = np.abs(a64) @ np.abs(w64)
