@@ -2,15 +2,16 @@
 // ReLU, and GIN's MLP): out = act(A . W + bias) on the matrix cores.
 //
 // Shape of the problem: A is tall (10^5..10^6 rows) and both d_in and d_out are small
-// (16..602), so each wavefront owns 32 rows of A and ALL output columns of its block:
-//   - A is read once, straight from HBM into registers in the MFMA operand layout
-//     (no LDS round trip: nobody else needs those rows);
-//   - W is staged slab by slab in LDS and shared by the block's four wavefronts;
+// (16..602).  A workgroup of four wavefronts covers a tile of (32*WM) rows x (NT*32*WN)
+// columns, WM*WN = 4; each wavefront owns 32 rows x NT*32 columns (NT <= 4, so that three
+// wavefronts fit a SIMD and the load phase of one overlaps the MFMA phase of another):
+//   - A goes straight from HBM into registers in the MFMA operand layout, the fragment of the
+//     next K slab being requested before the current slab is multiplied (no LDS round trip);
+//   - W is staged slab by slab in LDS and shared by the workgroup;
 //   - fp32 weights use v_mfma_f32_32x32x2_f32, bf16 weights v_mfma_f32_32x32x16_bf16,
 //     both with fp32 accumulators; bias, ReLU and the output rounding are fused.
-// MFMA sums over k in any order, so a lane may take whichever k values are contiguous for
-// it in memory as long as the A and W operands agree; that is what makes the direct loads
-// of A full-width.
+// MFMA sums over k in any order, so a lane takes whichever k values are contiguous for it in
+// memory as long as the A and W operands agree; that makes the direct loads of A full-width.
 #include <hip/hip_runtime.h>
 
 #include "mgg_internal.h"
@@ -25,8 +26,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int kWave = 64;
 constexpr int kWaves = 4;
 constexpr int kThreads = kWave * kWaves;
-constexpr int kRowsPerWave = 32;
-constexpr int kRowsPerBlock = kRowsPerWave * kWaves;
 
 struct UpdArgs {
     const void *a;
@@ -38,6 +37,8 @@ struct UpdArgs {
     int32_t relu;
     int32_t out_bf16;
     int32_t a_vec_ok;   // rows of A allow 16-byte loads
+    int32_t w_vec_ok;   // rows of W allow 16-byte loads
+    int32_t out_vec_ok; // rows of out allow 16-byte (fp32) / 8-byte (bf16) stores
 };
 
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
@@ -47,48 +48,204 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     return u >> 16;
 }
 
-// Epilogue shared by both paths.  In the 32x32 accumulator layout register r of lane
-// (j = lane % 32, h = lane / 32) is element (row 8*(r/4) + 4*h + r%4, column j).
+// Epilogue shared by both paths.  The kernels feed the W fragment as the first MFMA operand and
+// the A fragment as the second, so the 32x32 accumulator holds the TRANSPOSED tile: register r
+// of lane (m = lane % 32, h = lane / 32) is output row m, column 8*(r/4) + 4*h + r%4.  A lane
+// therefore owns four consecutive columns of one row per group of four registers and writes
+// them with one 16-byte (fp32) or 8-byte (bf16) store.
 template <int NT>
 __device__ __forceinline__ void store_tiles(const UpdArgs &p, const f32x16 (&acc)[NT], int64_t m0, int n0, int lane)
 {
-    const int j = lane & 31, h = lane >> 5;
+    const int m = lane & 31, h = lane >> 5;
+    const int64_t row = m0 + m;
+    if (row >= p.n_rows) return;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        const int col = n0 + t * 32 + j;
-        if (col >= p.d_out) continue;
-        const float b = p.bias ? p.bias[col] : 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t row = m0 + 8 * (r / 4) + 4 * h + (r % 4);
-            if (row >= p.n_rows) continue;
-            float v = acc[t][r] + b;
-            if (p.relu) v = v > 0.f ? v : 0.f;
-            if (p.out_bf16)
-                static_cast<uint16_t *>(p.out)[row * p.ld_out + col] = static_cast<uint16_t>(f32_to_bf16_bits(v));
-            else
-                static_cast<float *>(p.out)[row * p.ld_out + col] = v;
+        for (int q = 0; q < 4; ++q) {
+            const int col = n0 + t * 32 + 8 * q + 4 * h;
+            if (col >= p.d_out) continue;
+            float v[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[e] = acc[t][4 * q + e] + ((p.bias && col + e < p.d_out) ? p.bias[col + e] : 0.f);
+                if (p.relu) v[e] = v[e] > 0.f ? v[e] : 0.f;
+            }
+            const bool full = p.out_vec_ok && col + 3 < p.d_out;
+            if (p.out_bf16) {
+                uint16_t *o = static_cast<uint16_t *>(p.out) + row * p.ld_out + col;
+                if (full) {
+                    uint2 pk;
+                    pk.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
+                    pk.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
+                    *reinterpret_cast<uint2 *>(o) = pk;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (col + e < p.d_out) o[e] = static_cast<uint16_t>(f32_to_bf16_bits(v[e]));
+                }
+            } else {
+                float *o = static_cast<float *>(p.out) + row * p.ld_out + col;
+                if (full) {
+                    *reinterpret_cast<float4 *>(o) = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (col + e < p.d_out) o[e] = v[e];
+                }
+            }
+        }
+    }
+}
+
+// ---- staging W in LDS ---------------------------------------------------------------------------
+// Loads are issued in batches before any LDS store so that several are in flight per thread.
+// fp32: rows [k_begin, k_begin + n_k) and columns [nb, nb + NC) of W -> lds[n_k][NC], zeros
+// outside the matrix.
+template <int NC>
+__device__ __forceinline__ void fill_w_f32(float *lds, const float *W, int k_begin, int n_k, int nb, const UpdArgs &p)
+{
+    constexpr int B = 4;
+    if (p.w_vec_ok && nb + NC <= p.d_out) {
+        const int units = n_k * (NC / 4);
+        for (int base = threadIdx.x; base < units; base += kThreads * B) {
+            float4 v[B];
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const int id = base + b * kThreads;
+                v[b] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (id < units) {
+                    const int kk = id / (NC / 4), n4 = id % (NC / 4);
+                    if (k_begin + kk < p.d_in)
+                        v[b] = *reinterpret_cast<const float4 *>(W + static_cast<int64_t>(k_begin + kk) * p.d_out + nb + 4 * n4);
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const int id = base + b * kThreads;
+                if (id < units) reinterpret_cast<float4 *>(lds)[id] = v[b];
+            }
+        }
+    } else {
+        const int units = n_k * NC;
+        for (int base = threadIdx.x; base < units; base += kThreads * B) {
+            float v[B];
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const int id = base + b * kThreads;
+                v[b] = 0.f;
+                if (id < units) {
+                    const int k = k_begin + id / NC, n = nb + id % NC;
+                    if (k < p.d_in && n < p.d_out) v[b] = W[static_cast<int64_t>(k) * p.d_out + n];
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const int id = base + b * kThreads;
+                if (id < units) lds[id] = v[b];
+            }
+        }
+    }
+}
+
+// bf16: the same block of W, transposed -> lds[NC][ldw] (ldw even), element (n, k - k_begin).
+template <int NC>
+__device__ __forceinline__ void fill_w_bf16_t(uint16_t *lds, int ldw, const uint16_t *W, int k_begin, int n_k, int nb,
+                                              const UpdArgs &p)
+{
+    uint32_t *lds32 = reinterpret_cast<uint32_t *>(lds);
+    const int ldw2 = ldw / 2;
+    if (p.w_vec_ok && nb + NC <= p.d_out) {
+        // unit = a pair of k rows x 8 columns: two 16-byte loads, eight dword stores
+        constexpr int B = 2;
+        const int units = (n_k / 2) * (NC / 8);
+        for (int base = threadIdx.x; base < units; base += kThreads * B) {
+            uint4 lo[B], hi[B];
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const int id = base + b * kThreads;
+                lo[b] = make_uint4(0u, 0u, 0u, 0u);
+                hi[b] = make_uint4(0u, 0u, 0u, 0u);
+                if (id < units) {
+                    const int kp = id / (NC / 8), n8 = id % (NC / 8);
+                    const int k = k_begin + 2 * kp;
+                    const uint16_t *src = W + static_cast<int64_t>(k) * p.d_out + nb + 8 * n8;
+                    if (k < p.d_in) lo[b] = *reinterpret_cast<const uint4 *>(src);
+                    if (k + 1 < p.d_in) hi[b] = *reinterpret_cast<const uint4 *>(src + p.d_out);
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const int id = base + b * kThreads;
+                if (id < units) {
+                    const int kp = id / (NC / 8), n8 = id % (NC / 8);
+                    const uint32_t l[4] = {lo[b].x, lo[b].y, lo[b].z, lo[b].w}, u[4] = {hi[b].x, hi[b].y, hi[b].z, hi[b].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        lds32[(8 * n8 + 2 * e) * ldw2 + kp] = (l[e] & 0xffffu) | (u[e] << 16);
+                        lds32[(8 * n8 + 2 * e + 1) * ldw2 + kp] = (l[e] >> 16) | (u[e] & 0xffff0000u);
+                    }
+                }
+            }
+        }
+    } else {
+        constexpr int B = 4;
+        const int units = (n_k / 2) * NC;
+        for (int base = threadIdx.x; base < units; base += kThreads * B) {
+            uint32_t v[B];
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const int id = base + b * kThreads;
+                v[b] = 0u;
+                if (id < units) {
+                    const int k = k_begin + 2 * (id / NC), n = nb + id % NC;
+                    const uint32_t l = (k < p.d_in && n < p.d_out) ? W[static_cast<int64_t>(k) * p.d_out + n] : 0u;
+                    const uint32_t u = (k + 1 < p.d_in && n < p.d_out) ? W[static_cast<int64_t>(k + 1) * p.d_out + n] : 0u;
+                    v[b] = l | (u << 16);
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const int id = base + b * kThreads;
+                if (id < units) lds32[(id % NC) * ldw2 + id / NC] = v[b];
+            }
         }
     }
 }
 
 // ---- fp32 weights: v_mfma_f32_32x32x2_f32 ---------------------------------------------------
 // K slab of 32: lane (i, h) holds A[m0+i][k0 + 16h .. k0 + 16h + 15]; MFMA number c contracts
-// the k pair {k0 + c, k0 + 16 + c}.  W slab in LDS as [32][NT*32] floats.
-template <int NT>
+// the k pair {k0 + c, k0 + 16 + c}.  W slab in LDS as [32][NC] floats.
+// arow always points at a valid row (rows past the end are clamped to the last one and never
+// stored), so the only predicate is the wave-uniform "this slab is complete and aligned".
+__device__ __forceinline__ void load_a_f32(const UpdArgs &p, const float *arow, int kb, int k_slab_end, float (&af)[16])
+{
+    if (p.a_vec_ok && k_slab_end <= p.d_in) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 v = *reinterpret_cast<const float4 *>(arow + kb + 4 * q);
+            af[4 * q] = v.x; af[4 * q + 1] = v.y; af[4 * q + 2] = v.z; af[4 * q + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) af[e] = (kb + e < p.d_in) ? arow[kb + e] : 0.f;
+    }
+}
+
+template <int NT, int WN>
 __global__ __launch_bounds__(kThreads) void update_f32_kernel(const UpdArgs p)
 {
-    constexpr int BK = 32, NC = NT * 32;
-    __shared__ float w_lds[BK * NC];
+    constexpr int BK = 32, NC = NT * 32 * WN, WM = kWaves / WN;
+    __shared__ __attribute__((aligned(16))) float w_lds[BK * NC];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 31, h = lane >> 5;
-    const int64_t m0 = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock + wave * kRowsPerWave;
-    const int n0 = blockIdx.y * NC;
-    const float *A = static_cast<const float *>(p.a);
+    const int wm = wave / WN, wn = wave % WN;
+    const int64_t m0 = (static_cast<int64_t>(blockIdx.x) * WM + wm) * 32;
+    const int nb = blockIdx.y * NC;                 // first column of the workgroup
+    const int n0 = nb + wn * NT * 32;               // first column of this wavefront
     const float *W = static_cast<const float *>(p.w);
-    const int64_t row = m0 + i;
-    const bool row_ok = row < p.n_rows;
-    const float *arow = A + (row_ok ? row : 0) * p.ld_a;
+    const int64_t row = m0 + i < p.n_rows ? m0 + i : p.n_rows - 1;
+    const float *arow = static_cast<const float *>(p.a) + row * p.ld_a;
 
     f32x16 acc[NT];
 #pragma unroll
@@ -96,36 +253,23 @@ __global__ __launch_bounds__(kThreads) void update_f32_kernel(const UpdArgs p)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 
+    float af[16], an[16];
+    load_a_f32(p, arow, 16 * h, BK, af);
+#pragma unroll 1
     for (int k0 = 0; k0 < p.d_in; k0 += BK) {
-        // A fragment: 16 consecutive k of this lane's row
-        float af[16];
-        const int kb = k0 + 16 * h;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int k = kb + 4 * q;
-            if (row_ok && p.a_vec_ok && k + 3 < p.d_in) {
-                const float4 v = *reinterpret_cast<const float4 *>(arow + k);
-                af[4 * q] = v.x; af[4 * q + 1] = v.y; af[4 * q + 2] = v.z; af[4 * q + 3] = v.w;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) af[4 * q + e] = (row_ok && k + e < p.d_in) ? arow[k + e] : 0.f;
-            }
-        }
-        // W slab -> LDS (zeros outside the matrix)
+        if (k0 + BK < p.d_in) load_a_f32(p, arow, k0 + BK + 16 * h, k0 + 2 * BK, an);   // next slab's fragment
         __syncthreads();
-        for (int idx = threadIdx.x; idx < BK * NC; idx += kThreads) {
-            const int kk = idx / NC, nn = idx % NC;
-            const int k = k0 + kk, n = n0 + nn;
-            w_lds[idx] = (k < p.d_in && n < p.d_out) ? W[static_cast<int64_t>(k) * p.d_out + n] : 0.f;
-        }
+        fill_w_f32<NC>(w_lds, W, k0, BK, nb, p);
         __syncthreads();
 #pragma unroll
         for (int c = 0; c < 16; ++c) {
-            const float *wrow = w_lds + (16 * h + c) * NC + i;
+            const float *wrow = w_lds + (16 * h + c) * NC + wn * NT * 32 + i;
 #pragma unroll
             for (int t = 0; t < NT; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[c], wrow[t * 32], acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(wrow[t * 32], af[c], acc[t], 0, 0, 0);
         }
+#pragma unroll
+        for (int c = 0; c < 16; ++c) af[c] = an[c];
     }
     store_tiles<NT>(p, acc, m0, n0, lane);
 }
@@ -133,19 +277,67 @@ __global__ __launch_bounds__(kThreads) void update_f32_kernel(const UpdArgs p)
 // ---- bf16 weights: v_mfma_f32_32x32x16_bf16 -------------------------------------------------
 // K slab of 64: lane (i, h) holds A[m0+i][k0 + 32h .. k0 + 32h + 31] as four 8-element
 // operands; MFMA number c contracts k0 + 32h + 8c .. + 7 (both halves h at once).
-// W slab in LDS transposed, [NT*32][64 + 8] bf16, so a lane's 8 k-values are contiguous.
-template <int NT, bool A_BF16>
+// W slab in LDS transposed, [NC][64 + 8] bf16, so a lane's 8 k-values are contiguous.
+union Frag8 { uint32_t u[4]; bf16x8 v; };
+
+template <bool A_BF16>
+__device__ __forceinline__ void load_a_bf16(const UpdArgs &p, const void *arow_v, int kb, int k_slab_end, Frag8 (&af)[4])
+{
+    const bool full = p.a_vec_ok && k_slab_end <= p.d_in;      // wave-uniform
+    if constexpr (A_BF16) {
+        const uint16_t *arow = static_cast<const uint16_t *>(arow_v);
+        if (full) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(arow + kb + 8 * c);
+                af[c].u[0] = v.x; af[c].u[1] = v.y; af[c].u[2] = v.z; af[c].u[3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int k = kb + 8 * c + 2 * e;
+                    const uint32_t lo = k < p.d_in ? arow[k] : 0u;
+                    const uint32_t hi = k + 1 < p.d_in ? arow[k + 1] : 0u;
+                    af[c].u[e] = lo | (hi << 16);
+                }
+        }
+    } else {
+        const float *arow = static_cast<const float *>(arow_v);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int k = kb + 8 * c;
+            float f[8];
+            if (full) {
+                const float4 v0 = *reinterpret_cast<const float4 *>(arow + k);
+                const float4 v1 = *reinterpret_cast<const float4 *>(arow + k + 4);
+                f[0] = v0.x; f[1] = v0.y; f[2] = v0.z; f[3] = v0.w; f[4] = v1.x; f[5] = v1.y; f[6] = v1.z; f[7] = v1.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[e] = k + e < p.d_in ? arow[k + e] : 0.f;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) af[c].u[e] = f32_to_bf16_bits(f[2 * e]) | (f32_to_bf16_bits(f[2 * e + 1]) << 16);
+        }
+    }
+}
+
+template <int NT, int WN, bool A_BF16>
 __global__ __launch_bounds__(kThreads) void update_bf16_kernel(const UpdArgs p)
 {
-    constexpr int BK = 64, NC = NT * 32, LDW = BK + 8;
+    constexpr int BK = 64, NC = NT * 32 * WN, LDW = BK + 8, WM = kWaves / WN;
     __shared__ __attribute__((aligned(16))) uint16_t w_lds[NC * LDW];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 31, h = lane >> 5;
-    const int64_t m0 = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock + wave * kRowsPerWave;
-    const int n0 = blockIdx.y * NC;
+    const int wm = wave / WN, wn = wave % WN;
+    const int64_t m0 = (static_cast<int64_t>(blockIdx.x) * WM + wm) * 32;
+    const int nb = blockIdx.y * NC;
+    const int n0 = nb + wn * NT * 32;
     const uint16_t *W = static_cast<const uint16_t *>(p.w);
-    const int64_t row = m0 + i;
-    const bool row_ok = row < p.n_rows;
+    const int64_t row = m0 + i < p.n_rows ? m0 + i : p.n_rows - 1;
+    const void *arow = A_BF16 ? static_cast<const void *>(static_cast<const uint16_t *>(p.a) + row * p.ld_a)
+                              : static_cast<const void *>(static_cast<const float *>(p.a) + row * p.ld_a);
 
     f32x16 acc[NT];
 #pragma unroll
@@ -153,75 +345,158 @@ __global__ __launch_bounds__(kThreads) void update_bf16_kernel(const UpdArgs p)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 
+    Frag8 af[4], an[4];
+    load_a_bf16<A_BF16>(p, arow, 32 * h, BK, af);
+#pragma unroll 1
     for (int k0 = 0; k0 < p.d_in; k0 += BK) {
-        union { uint32_t u[4]; bf16x8 v; } af[4];
-        const int kb = k0 + 32 * h;
-        if constexpr (A_BF16) {
-            const uint16_t *arow = static_cast<const uint16_t *>(p.a) + (row_ok ? row : 0) * p.ld_a;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int k = kb + 8 * c;
-                if (row_ok && p.a_vec_ok && k + 7 < p.d_in) {
-                    const uint4 v = *reinterpret_cast<const uint4 *>(arow + k);
-                    af[c].u[0] = v.x; af[c].u[1] = v.y; af[c].u[2] = v.z; af[c].u[3] = v.w;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const uint32_t lo = (row_ok && k + 2 * e < p.d_in) ? arow[k + 2 * e] : 0u;
-                        const uint32_t hi = (row_ok && k + 2 * e + 1 < p.d_in) ? arow[k + 2 * e + 1] : 0u;
-                        af[c].u[e] = lo | (hi << 16);
-                    }
-                }
-            }
-        } else {
-            const float *arow = static_cast<const float *>(p.a) + (row_ok ? row : 0) * p.ld_a;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int k = kb + 8 * c;
-                float f[8];
-                if (row_ok && p.a_vec_ok && k + 7 < p.d_in) {
-                    const float4 v0 = *reinterpret_cast<const float4 *>(arow + k);
-                    const float4 v1 = *reinterpret_cast<const float4 *>(arow + k + 4);
-                    f[0] = v0.x; f[1] = v0.y; f[2] = v0.z; f[3] = v0.w; f[4] = v1.x; f[5] = v1.y; f[6] = v1.z; f[7] = v1.w;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) f[e] = (row_ok && k + e < p.d_in) ? arow[k + e] : 0.f;
-                }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) af[c].u[e] = f32_to_bf16_bits(f[2 * e]) | (f32_to_bf16_bits(f[2 * e + 1]) << 16);
-            }
-        }
-        // W slab -> LDS, transposed: thread takes a k pair of one column, writes one dword
+        if (k0 + BK < p.d_in) load_a_bf16<A_BF16>(p, arow, k0 + BK + 32 * h, k0 + 2 * BK, an);
         __syncthreads();
-        for (int idx = threadIdx.x; idx < (BK / 2) * NC; idx += kThreads) {
-            const int kp = idx / NC, nn = idx % NC;
-            const int k = k0 + 2 * kp, n = n0 + nn;
-            const uint32_t lo = (k < p.d_in && n < p.d_out) ? W[static_cast<int64_t>(k) * p.d_out + n] : 0u;
-            const uint32_t hi = (k + 1 < p.d_in && n < p.d_out) ? W[static_cast<int64_t>(k + 1) * p.d_out + n] : 0u;
-            *reinterpret_cast<uint32_t *>(&w_lds[nn * LDW + 2 * kp]) = lo | (hi << 16);
-        }
+        fill_w_bf16_t<NC>(w_lds, LDW, W, k0, BK, nb, p);
         __syncthreads();
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 union { uint4 q; bf16x8 v; } bw;
-                bw.q = *reinterpret_cast<const uint4 *>(&w_lds[(t * 32 + i) * LDW + 32 * h + 8 * c]);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[c].v, bw.v, acc[t], 0, 0, 0);
+                bw.q = *reinterpret_cast<const uint4 *>(&w_lds[(wn * NT * 32 + t * 32 + i) * LDW + 32 * h + 8 * c]);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw.v, af[c].v, acc[t], 0, 0, 0);
             }
         }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) af[c] = an[c];
     }
     store_tiles<NT>(p, acc, m0, n0, lane);
+}
+
+
+// ---- W resident in LDS (small d_in * d_out) ---------------------------------------------------
+// When the whole weight matrix fits 64 KB of LDS it is staged once per workgroup, and every
+// wavefront then walks over many 32-row tiles of A on its own: no barrier in the main loop, the
+// A fragment of the next slab (or of the next tile) in flight while the current one is
+// multiplied.  The grid is sized to the chip (a few workgroups per CU), not to the matrix.
+extern __shared__ __attribute__((aligned(16))) unsigned char w_res[];
+
+template <int NT>
+__global__ __launch_bounds__(kThreads) void update_f32_resident_kernel(const UpdArgs p)
+{
+    constexpr int BK = 32, NC = NT * 32;
+    float *w_lds = reinterpret_cast<float *>(w_res);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 31, h = lane >> 5;
+    const int n_slabs = (p.d_in + BK - 1) / BK;
+    const float *W = static_cast<const float *>(p.w);
+    fill_w_f32<NC>(w_lds, W, 0, n_slabs * BK, 0, p);
+    __syncthreads();
+
+    const int64_t n_tiles = (p.n_rows + 31) / 32, stride = static_cast<int64_t>(gridDim.x) * kWaves;
+    int64_t tile = static_cast<int64_t>(blockIdx.x) * kWaves + wave;
+    if (tile >= n_tiles) return;
+    auto row_ptr_of = [&](int64_t t) {
+        const int64_t r = t * 32 + i < p.n_rows ? t * 32 + i : p.n_rows - 1;
+        return static_cast<const float *>(p.a) + r * p.ld_a;
+    };
+    const float *arow = row_ptr_of(tile);
+    float af[16], an[16];
+    load_a_f32(p, arow, 16 * h, BK, af);
+    while (tile < n_tiles) {
+        f32x16 acc[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+        const int64_t next_tile = tile + stride;
+        const float *next_row = row_ptr_of(next_tile < n_tiles ? next_tile : tile);
+#pragma unroll 1
+        for (int s = 0; s < n_slabs; ++s) {
+            if (s + 1 < n_slabs) load_a_f32(p, arow, (s + 1) * BK + 16 * h, (s + 2) * BK, an);
+            else if (next_tile < n_tiles) load_a_f32(p, next_row, 16 * h, BK, an);
+#pragma unroll
+            for (int c = 0; c < 16; ++c) {
+                const float *wrow = w_lds + (s * BK + 16 * h + c) * NC + i;
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(wrow[t * 32], af[c], acc[t], 0, 0, 0);
+            }
+#pragma unroll
+            for (int c = 0; c < 16; ++c) af[c] = an[c];
+        }
+        store_tiles<NT>(p, acc, tile * 32, 0, lane);
+        tile = next_tile;
+        arow = next_row;
+    }
+}
+
+template <int NT, bool A_BF16>
+__global__ __launch_bounds__(kThreads) void update_bf16_resident_kernel(const UpdArgs p)
+{
+    constexpr int BK = 64, NC = NT * 32;
+    uint16_t *w_lds = reinterpret_cast<uint16_t *>(w_res);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 31, h = lane >> 5;
+    const int n_slabs = (p.d_in + BK - 1) / BK;
+    const int ldw = n_slabs * BK + 8;                       // padded row of the transposed copy
+    const uint16_t *W = static_cast<const uint16_t *>(p.w);
+    fill_w_bf16_t<NC>(w_lds, ldw, W, 0, n_slabs * BK, 0, p);
+    __syncthreads();
+
+    const int64_t n_tiles = (p.n_rows + 31) / 32, stride = static_cast<int64_t>(gridDim.x) * kWaves;
+    int64_t tile = static_cast<int64_t>(blockIdx.x) * kWaves + wave;
+    if (tile >= n_tiles) return;
+    auto row_ptr_of = [&](int64_t t) -> const void * {
+        const int64_t r = t * 32 + i < p.n_rows ? t * 32 + i : p.n_rows - 1;
+        if constexpr (A_BF16) return static_cast<const uint16_t *>(p.a) + r * p.ld_a;
+        else return static_cast<const float *>(p.a) + r * p.ld_a;
+    };
+    const void *arow = row_ptr_of(tile);
+    Frag8 af[4], an[4];
+    load_a_bf16<A_BF16>(p, arow, 32 * h, BK, af);
+    while (tile < n_tiles) {
+        f32x16 acc[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+        const int64_t next_tile = tile + stride;
+        const void *next_row = row_ptr_of(next_tile < n_tiles ? next_tile : tile);
+#pragma unroll 1
+        for (int s = 0; s < n_slabs; ++s) {
+            if (s + 1 < n_slabs) load_a_bf16<A_BF16>(p, arow, (s + 1) * BK + 32 * h, (s + 2) * BK, an);
+            else if (next_tile < n_tiles) load_a_bf16<A_BF16>(p, next_row, 32 * h, BK, an);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    union { uint4 q; bf16x8 v; } bw;
+                    bw.q = *reinterpret_cast<const uint4 *>(&w_lds[(t * 32 + i) * ldw + s * BK + 32 * h + 8 * c]);
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw.v, af[c].v, acc[t], 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) af[c] = an[c];
+        }
+        store_tiles<NT>(p, acc, tile * 32, 0, lane);
+        tile = next_tile;
+        arow = next_row;
+    }
 }
 
 inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
 template <int NT>
-hipError_t launch_nt(const UpdArgs &p, bool w_bf16, bool a_bf16, dim3 grid, hipStream_t s)
+hipError_t launch_resident(const UpdArgs &p, bool w_bf16, bool a_bf16, int blocks, size_t lds_bytes, hipStream_t s)
 {
-    if (!w_bf16) hipLaunchKernelGGL(update_f32_kernel<NT>, grid, dim3(kThreads), 0, s, p);
-    else if (a_bf16) hipLaunchKernelGGL((update_bf16_kernel<NT, true>), grid, dim3(kThreads), 0, s, p);
-    else hipLaunchKernelGGL((update_bf16_kernel<NT, false>), grid, dim3(kThreads), 0, s, p);
+    if (!w_bf16) hipLaunchKernelGGL((update_f32_resident_kernel<NT>), dim3(blocks), dim3(kThreads), lds_bytes, s, p);
+    else if (a_bf16) hipLaunchKernelGGL((update_bf16_resident_kernel<NT, true>), dim3(blocks), dim3(kThreads), lds_bytes, s, p);
+    else hipLaunchKernelGGL((update_bf16_resident_kernel<NT, false>), dim3(blocks), dim3(kThreads), lds_bytes, s, p);
+    return hipGetLastError();
+}
+
+template <int NT, int WN>
+hipError_t launch_shape(const UpdArgs &p, bool w_bf16, bool a_bf16, dim3 grid, hipStream_t s)
+{
+    if (!w_bf16) hipLaunchKernelGGL((update_f32_kernel<NT, WN>), grid, dim3(kThreads), 0, s, p);
+    else if (a_bf16) hipLaunchKernelGGL((update_bf16_kernel<NT, WN, true>), grid, dim3(kThreads), 0, s, p);
+    else hipLaunchKernelGGL((update_bf16_kernel<NT, WN, false>), grid, dim3(kThreads), 0, s, p);
     return hipGetLastError();
 }
 
@@ -240,21 +515,44 @@ mgg_status_t launch_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, i
     p.relu = act == MGG_ACT_RELU;
     p.out_bf16 = out_dtype == MGG_BF16;
     p.a_vec_ok = aligned16(a) && (ld_a % (a_bf16 ? 8 : 4) == 0);
+    p.out_vec_ok = (ld_out % 4 == 0) && (reinterpret_cast<uintptr_t>(out) % (out_dtype == MGG_BF16 ? 8 : 16) == 0);
+    p.w_vec_ok = aligned16(w) && (d_out % (w_bf16 ? 8 : 4) == 0);
 
-    // columns per block: all of them up to 256 (fp32) / 256 (bf16); wider outputs tile over grid.y
-    int nt = 1;
-    while (nt * 32 < d_out && nt < 8) nt <<= 1;
-    const int nc = nt * 32;
-    const int64_t gx = (n_rows + kRowsPerBlock - 1) / kRowsPerBlock;
+    // tiles of 32 columns per wavefront (1, 2 or 4) and wavefronts side by side (1 or 2);
+    // outputs wider than 256 columns tile over grid.y
+    int nt = 1, wn = 1;
+    if (d_out > 128) { nt = 4; wn = 2; }
+    else if (d_out > 64) nt = 4;
+    else if (d_out > 32) nt = 2;
+    // small weight matrices stay resident in LDS and the grid is sized to the chip
+    if (wn == 1) {
+        const size_t k_pad = w_bf16 ? (static_cast<size_t>(d_in) + 63) / 64 * 64 : (static_cast<size_t>(d_in) + 31) / 32 * 32;
+        const size_t lds_bytes = w_bf16 ? static_cast<size_t>(nt) * 32 * (k_pad + 8) * 2 : k_pad * nt * 32 * 4;
+        if (lds_bytes <= 64 * 1024) {
+            int dev = 0, cus = 256;
+            if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+            int per_cu = static_cast<int>((160 * 1024) / (lds_bytes + 512));
+            per_cu = per_cu < 1 ? 1 : (per_cu > (nt == 4 ? 3 : 4) ? (nt == 4 ? 3 : 4) : per_cu);
+            const int64_t n_tiles = (n_rows + 31) / 32;
+            const int64_t want = (n_tiles + kWaves - 1) / kWaves;
+            const int blocks = static_cast<int>(want < static_cast<int64_t>(cus) * per_cu ? want : static_cast<int64_t>(cus) * per_cu);
+            hipError_t e;
+            if (nt == 1) e = launch_resident<1>(p, w_bf16, a_bf16, blocks, lds_bytes, stream);
+            else if (nt == 2) e = launch_resident<2>(p, w_bf16, a_bf16, blocks, lds_bytes, stream);
+            else e = launch_resident<4>(p, w_bf16, a_bf16, blocks, lds_bytes, stream);
+            if (e != hipSuccess) return hip_fail(e, "update kernel launch");
+            return MGG_OK;
+        }
+    }
+    const int nc = nt * 32 * wn, rows_per_block = 32 * (kWaves / wn);
+    const int64_t gx = (n_rows + rows_per_block - 1) / rows_per_block;
     if (gx > INT32_MAX) return fail(MGG_ERR_UNSUPPORTED, "too many rows for one launch");
     dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>((d_out + nc - 1) / nc));
     hipError_t e;
-    switch (nt) {
-        case 1: e = launch_nt<1>(p, w_bf16, a_bf16, grid, stream); break;
-        case 2: e = launch_nt<2>(p, w_bf16, a_bf16, grid, stream); break;
-        case 4: e = launch_nt<4>(p, w_bf16, a_bf16, grid, stream); break;
-        default: e = launch_nt<8>(p, w_bf16, a_bf16, grid, stream); break;
-    }
+    if (nt == 1) e = launch_shape<1, 1>(p, w_bf16, a_bf16, grid, stream);
+    else if (nt == 2) e = launch_shape<2, 1>(p, w_bf16, a_bf16, grid, stream);
+    else if (wn == 1) e = launch_shape<4, 1>(p, w_bf16, a_bf16, grid, stream);
+    else e = launch_shape<4, 2>(p, w_bf16, a_bf16, grid, stream);
     if (e != hipSuccess) return hip_fail(e, "update kernel launch");
     return MGG_OK;
 }
