@@ -50,7 +50,7 @@ typedef struct mgg_partition mgg_partition_t;   /* opaque, library-owned */
 /* Knobs of the partition build.  They are the paper's tuning parameters (section 6):
  * ps = neighbours per neighbour partition (1..64), dist = how many (local, remote)
  * partition pairs one wavefront work item covers (1..1024).  0 selects the default
- * (ps 32, dist 16, short_max 16).  Rows with at most short_max neighbours in total
+ * (ps 32, dist 16, short_max 16, xcd_min_deg 256).  Rows with at most short_max neighbours in total
  * are handled several per wavefront; short_max < 0 disables that bin. */
 typedef struct {
     int32_t ps;
@@ -59,6 +59,10 @@ typedef struct {
     int32_t host_only;   /* nonzero: build on the host only, never touch the GPU (for
                             checks of the integer structures); device calls on such a
                             partition fail with MGG_ERR_INVALID_ARG */
+    int32_t xcd_min_deg; /* rows with at least this many neighbours have their neighbour lists
+                            regrouped into 8 source classes (a hash of the table row), one
+                            per XCD, so each XCD's L2 serves one eighth of the table for
+                            them; 0 = library default, negative = off */
 } mgg_build_opts_t;
 
 typedef struct {
@@ -66,9 +70,10 @@ typedef struct {
     int64_t nnz_local, nnz_remote, num_halo;
     int32_t num_parts, part_id;
     int32_t ps, dist, short_max, on_device;
+    int32_t xcd_min_deg, reserved;
     int64_t n_groups_local, n_groups_remote;  /* neighbour partitions of the two CSRs        */
     int64_t n_short_rows;                     /* rows handled several per wavefront          */
-    int64_t n_items;                          /* wavefront work items (all non-short rows)   */
+    int64_t n_items;                          /* wavefront work items incl. padding items     */
     int64_t n_split_rows, n_split_items;      /* rows cut into > 1 item, and those items     */
 } mgg_partition_info_t;
 
@@ -86,9 +91,11 @@ typedef struct {
     int32_t *grp_local_row, *grp_local_start, *grp_local_end;      /* [n_groups_local]       */
     int32_t *grp_remote_row, *grp_remote_start, *grp_remote_end;   /* [n_groups_remote]      */
     int32_t *short_rows;      /* [n_short_rows] owned-row indices of the short bin           */
-    int32_t *item_row;        /* [n_items] owned row of each wavefront work item             */
-    int32_t *item_lbeg, *item_lend;   /* [n_items] range in local_col                        */
-    int32_t *item_rbeg, *item_rend;   /* [n_items] range in remote_col                       */
+    int32_t *sched_local_col; /* [nnz_local]  local_col in the order the kernel walks it: the  */
+    int32_t *sched_remote_col;/* [nnz_remote] same rows, regrouped rows sorted by source class  */
+    int32_t *item_row;        /* [n_items] owned row of each work item; -1 = padding item      */
+    int32_t *item_lbeg, *item_lend;   /* [n_items] range in sched_local_col                  */
+    int32_t *item_rbeg, *item_rend;   /* [n_items] range in sched_remote_col                 */
     int32_t *item_slot;       /* [n_items] -1: the item is the whole row; else partial slot  */
 } mgg_partition_arrays_t;
 

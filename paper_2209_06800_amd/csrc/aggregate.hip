@@ -315,6 +315,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
         const int item_id = __builtin_amdgcn_readfirstlane(static_cast<int>(blockIdx.x) * kWavesPerBlock + wave);
         if (item_id >= a.n_items) return;
         const WorkItem it = a.items[item_id];
+        if (it.row < 0) return;                         // padding item
         const int ps = a.ps;
         const int n_l = it.lend - it.lbeg, n_r = it.rend - it.rbeg;
         const int g_l = (n_l + ps - 1) / ps, g_r = (n_r + ps - 1) / ps;

@@ -14,7 +14,7 @@ namespace mgg {
 // One wavefront work item: a run of neighbour partitions of one owned row, from the local
 // list and from the remote list (section 5.1: a warp handles pairs of local / remote
 // partitions).  slot < 0: the item covers the whole row and writes the final value;
-// slot >= 0: it writes a raw partial sum into scratch row `slot`.
+// slot >= 0: it writes a raw partial sum into scratch row `slot`.  row < 0: padding, nothing to do.
 struct WorkItem {
     int32_t row;
     int32_t lbeg, lend;   // range in local_col
@@ -33,6 +33,10 @@ struct SplitRow {
     int32_t pad;
 };
 
+constexpr int kXcd = 8;             // accelerator complex dies of an MI355X, each with its own L2
+constexpr int kItemsPerGroup = 4;   // work items (wavefronts) per workgroup of the aggregation kernel
+constexpr int kDefaultXcdMinDeg = 256;
+
 struct DeviceArrays {
     int32_t *local_row_ptr = nullptr, *local_col = nullptr;
     int32_t *remote_row_ptr = nullptr, *remote_col = nullptr;
@@ -49,9 +53,10 @@ struct DeviceArrays {
 struct mgg_partition {
     int64_t num_nodes = 0, lb = 0, ub = 0, n_own = 0;
     int32_t num_parts = 1, part_id = 0;
-    int32_t ps = 32, dist = 16, short_max = 16;
+    int32_t ps = 32, dist = 16, short_max = 16, xcd_min_deg = -1;
     int device = -1;  // HIP device the arrays live on; -1 = host only
     std::vector<int32_t> local_row_ptr, local_col, remote_row_ptr, remote_col;
+    std::vector<int32_t> sched_local_col, sched_remote_col;   // device order of the columns (empty: same as above)
     std::vector<int32_t> halo_gid, deg_own, deg_halo;
     std::vector<int64_t> halo_peer_ptr;
     std::vector<float> dinv_own, dinv_halo;

@@ -59,9 +59,9 @@ static mgg_status_t upload_all(mgg_partition *p)
     p->device = dev;
     mgg_status_t s;
     if ((s = upload(p->local_row_ptr, &p->d.local_row_ptr)) != MGG_OK) return s;
-    if ((s = upload(p->local_col, &p->d.local_col)) != MGG_OK) return s;
+    if ((s = upload(p->sched_local_col.empty() ? p->local_col : p->sched_local_col, &p->d.local_col)) != MGG_OK) return s;
     if ((s = upload(p->remote_row_ptr, &p->d.remote_row_ptr)) != MGG_OK) return s;
-    if ((s = upload(p->remote_col, &p->d.remote_col)) != MGG_OK) return s;
+    if ((s = upload(p->sched_remote_col.empty() ? p->remote_col : p->sched_remote_col, &p->d.remote_col)) != MGG_OK) return s;
     if ((s = upload(p->dinv_own, &p->d.dinv_own)) != MGG_OK) return s;
     if ((s = upload(p->dinv_halo, &p->d.dinv_halo)) != MGG_OK) return s;
     if ((s = upload(p->short_rows, &p->d.short_rows)) != MGG_OK) return s;
@@ -71,6 +71,10 @@ static mgg_status_t upload_all(mgg_partition *p)
 }
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Class of an embedding-table row (a multiplicative hash, so that classes are balanced even when
+// hubs crowd the low ids).
+static inline int source_class(int32_t row) { return static_cast<int>((static_cast<uint32_t>(row) * 0x9E3779B1u) >> 29); }
 
 static void export_groups(const std::vector<int32_t> &rp, int32_t ps, int32_t *row, int32_t *start, int32_t *end)
 {
@@ -109,12 +113,13 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
     if (num_nodes > INT32_MAX - 1) return fail(MGG_ERR_UNSUPPORTED, "more than 2^31-2 nodes");
     if (num_parts < 1 || part_id < 0 || part_id >= num_parts)
         return fail(MGG_ERR_INVALID_ARG, "part_id %d outside [0, %d)", part_id, num_parts);
-    int32_t ps = 32, dist = 16, short_max = 16, host_only = 0;
+    int32_t ps = 32, dist = 16, short_max = 16, host_only = 0, xcd_min_deg = kDefaultXcdMinDeg;
     if (opts) {
         if (opts->ps) ps = opts->ps;
         if (opts->dist) dist = opts->dist;
         if (opts->short_max) short_max = opts->short_max;
         host_only = opts->host_only;
+        if (opts->xcd_min_deg) xcd_min_deg = opts->xcd_min_deg;
     }
     if (ps < 1 || ps > 64) return fail(MGG_ERR_INVALID_ARG, "ps %d outside [1, 64]", ps);
     if (dist < 1 || dist > 1024) return fail(MGG_ERR_INVALID_ARG, "dist %d outside [1, 1024]", dist);
@@ -151,7 +156,7 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
     try {
         p->num_nodes = num_nodes; p->lb = lb; p->ub = ub; p->n_own = n_own;
         p->num_parts = num_parts; p->part_id = part_id;
-        p->ps = ps; p->dist = dist; p->short_max = short_max;
+        p->ps = ps; p->dist = dist; p->short_max = short_max; p->xcd_min_deg = xcd_min_deg;
 
         // ---- pass 1: count local / remote per owned row, mark halo nodes -----------------
         std::vector<uint8_t> is_halo(static_cast<size_t>(num_nodes), 0);
@@ -215,9 +220,29 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
         // ---- work decomposition ----------------------------------------------------------
         // short rows: several per wavefront; whole rows: one item; long rows: cut at
         // multiples of dist neighbour partitions, item k pairing local run k with remote run k.
+        // Rows with at least xcd_min_deg neighbours are first regrouped by source class (a hash
+        // of the table row id, kXcd classes): each class gets its own items, and the launch order
+        // below hands all items of class c to XCD c, so that each XCD's L2 only has to hold one
+        // eighth of the embedding rows those heavy rows touch.
         const int64_t run = static_cast<int64_t>(ps) * dist;   // neighbours per run
-        std::vector<WorkItem> whole;
+        const bool use_classes = xcd_min_deg > 0;
+        if (use_classes) { p->sched_local_col = p->local_col; p->sched_remote_col = p->remote_col; }
+        std::vector<std::vector<WorkItem>> queue(kXcd);
+        std::vector<int64_t> queue_work(kXcd, 0);
+        std::vector<WorkItem> light;
         std::vector<std::vector<int32_t>> by_len(short_max >= 0 ? short_max + 1 : 0);
+        auto item_work = [](const WorkItem &it) { return static_cast<int64_t>(it.lend - it.lbeg) + (it.rend - it.rbeg) + 8; };
+        auto regroup = [](std::vector<int32_t> &col, int32_t b, int32_t e, int32_t (&cut)[kXcd + 1]) {
+            // stable counting sort of col[b, e) by class; cut[c] = start of class c
+            int32_t cnt[kXcd] = {0};
+            for (int32_t i = b; i < e; ++i) ++cnt[source_class(col[i])];
+            cut[0] = b;
+            for (int c = 0; c < kXcd; ++c) cut[c + 1] = cut[c] + cnt[c];
+            std::vector<int32_t> tmp(col.begin() + b, col.begin() + e);
+            int32_t pos[kXcd];
+            for (int c = 0; c < kXcd; ++c) pos[c] = cut[c];
+            for (int32_t u : tmp) col[pos[source_class(u)]++] = u;
+        };
         for (int64_t v = 0; v < n_own; ++v) {
             const int32_t l0 = p->local_row_ptr[v], l1 = p->local_row_ptr[v + 1];
             const int32_t r0 = p->remote_row_ptr[v], r1 = p->remote_row_ptr[v + 1];
@@ -225,26 +250,68 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
             p->n_groups_local += ceil_div(dl, ps);
             p->n_groups_remote += ceil_div(dr, ps);
             if (short_max >= 0 && dl + dr <= short_max) { by_len[dl + dr].push_back(static_cast<int32_t>(v)); continue; }
-            const int64_t n_it = std::max<int64_t>(1, std::max(ceil_div(dl, run), ceil_div(dr, run)));
-            if (n_it == 1) {
-                whole.push_back(WorkItem{static_cast<int32_t>(v), l0, l1, r0, r1, -1, 0, 0});
-                continue;
+            // the pieces of this row: one per class if it is regrouped, otherwise the whole row
+            int32_t lcut[kXcd + 1], rcut[kXcd + 1];
+            int n_piece = 1;
+            if (use_classes && dl + dr >= xcd_min_deg) {
+                regroup(p->sched_local_col, l0, l1, lcut);
+                regroup(p->sched_remote_col, r0, r1, rcut);
+                n_piece = kXcd;
+            } else {
+                lcut[0] = l0; lcut[1] = l1; rcut[0] = r0; rcut[1] = r1;
             }
-            SplitRow sr{static_cast<int32_t>(v), static_cast<int32_t>(p->n_split_items), static_cast<int32_t>(n_it), 0};
-            p->split_rows.push_back(sr);
-            for (int64_t k = 0; k < n_it; ++k) {
-                WorkItem it;
-                it.row = static_cast<int32_t>(v);
-                it.lbeg = static_cast<int32_t>(std::min<int64_t>(l0 + k * run, l1));
-                it.lend = static_cast<int32_t>(std::min<int64_t>(l0 + (k + 1) * run, l1));
-                it.rbeg = static_cast<int32_t>(std::min<int64_t>(r0 + k * run, r1));
-                it.rend = static_cast<int32_t>(std::min<int64_t>(r0 + (k + 1) * run, r1));
-                it.slot = static_cast<int32_t>(p->n_split_items++);
-                it.pad0 = it.pad1 = 0;
-                p->items.push_back(it);                    // heavy items go first in launch order
+            std::vector<std::pair<WorkItem, int>> row_items;   // item, class (-1 = any XCD)
+            for (int c = 0; c < n_piece; ++c) {
+                const int64_t pl = lcut[c + 1] - lcut[c], pr = rcut[c + 1] - rcut[c];
+                if (n_piece > 1 && pl + pr == 0) continue;
+                const int64_t n_it = std::max<int64_t>(1, std::max(ceil_div(pl, run), ceil_div(pr, run)));
+                for (int64_t k = 0; k < n_it; ++k) {
+                    WorkItem it;
+                    it.row = static_cast<int32_t>(v);
+                    it.lbeg = static_cast<int32_t>(std::min<int64_t>(lcut[c] + k * run, lcut[c + 1]));
+                    it.lend = static_cast<int32_t>(std::min<int64_t>(lcut[c] + (k + 1) * run, lcut[c + 1]));
+                    it.rbeg = static_cast<int32_t>(std::min<int64_t>(rcut[c] + k * run, rcut[c + 1]));
+                    it.rend = static_cast<int32_t>(std::min<int64_t>(rcut[c] + (k + 1) * run, rcut[c + 1]));
+                    it.slot = -1;
+                    it.pad0 = it.pad1 = 0;
+                    row_items.emplace_back(it, n_piece > 1 ? c : -1);
+                }
+            }
+            if (row_items.size() > 1) {                      // partial sums + fix-up
+                SplitRow sr{static_cast<int32_t>(v), static_cast<int32_t>(p->n_split_items), static_cast<int32_t>(row_items.size()), 0};
+                p->split_rows.push_back(sr);
+                for (auto &ri : row_items) ri.first.slot = static_cast<int32_t>(p->n_split_items++);
+            }
+            for (auto &ri : row_items) {
+                if (ri.second >= 0) { queue[ri.second].push_back(ri.first); queue_work[ri.second] += item_work(ri.first); }
+                else if (ri.first.slot >= 0) p->items.push_back(ri.first);     // cut, not regrouped: heavy, goes first
+                else light.push_back(ri.first);
             }
         }
-        p->items.insert(p->items.end(), whole.begin(), whole.end());
+        if (!use_classes) {
+            p->items.insert(p->items.end(), light.begin(), light.end());
+        } else {
+            // cut-but-not-regrouped items (none when xcd_min_deg <= ps*dist) and whole-row items fill
+            // the queues so that every XCD gets the same amount of work
+            std::vector<WorkItem> rest;
+            rest.swap(p->items);
+            rest.insert(rest.end(), light.begin(), light.end());
+            for (const WorkItem &it : rest) {
+                const int c = static_cast<int>(std::min_element(queue_work.begin(), queue_work.end()) - queue_work.begin());
+                queue[c].push_back(it);
+                queue_work[c] += item_work(it);
+            }
+            // launch order: workgroup b (four items) runs on XCD b mod kXcd; pad with empty items
+            size_t longest = 0;
+            for (auto &q : queue) longest = std::max(longest, q.size());
+            longest = (longest + kItemsPerGroup - 1) / kItemsPerGroup * kItemsPerGroup;
+            const WorkItem dummy{-1, 0, 0, 0, 0, -1, 0, 0};
+            for (auto &q : queue) q.resize(longest, dummy);
+            p->items.reserve(longest * kXcd);
+            for (size_t g = 0; g < longest; g += kItemsPerGroup)
+                for (int c = 0; c < kXcd; ++c)
+                    p->items.insert(p->items.end(), queue[c].begin() + g, queue[c].begin() + g + kItemsPerGroup);
+        }
         for (int32_t len = short_max; len >= 0; --len)         // longest first, isolated rows last
             p->short_rows.insert(p->short_rows.end(), by_len[len].begin(), by_len[len].end());
     } catch (const std::bad_alloc &) {
@@ -270,6 +337,7 @@ mgg_status_t mgg_partition_info(const mgg_partition_t *p, mgg_partition_info_t *
     o->num_halo = static_cast<int64_t>(p->halo_gid.size());
     o->num_parts = p->num_parts; o->part_id = p->part_id;
     o->ps = p->ps; o->dist = p->dist; o->short_max = p->short_max; o->on_device = p->device >= 0;
+    o->xcd_min_deg = p->xcd_min_deg;
     o->n_groups_local = p->n_groups_local; o->n_groups_remote = p->n_groups_remote;
     o->n_short_rows = static_cast<int64_t>(p->short_rows.size());
     o->n_items = static_cast<int64_t>(p->items.size());
@@ -294,6 +362,8 @@ mgg_status_t mgg_partition_export(const mgg_partition_t *p, mgg_partition_arrays
     if (a->grp_remote_row || a->grp_remote_start || a->grp_remote_end)
         export_groups(p->remote_row_ptr, p->ps, a->grp_remote_row, a->grp_remote_start, a->grp_remote_end);
     copy_out(p->short_rows, a->short_rows);
+    copy_out(p->sched_local_col.empty() ? p->local_col : p->sched_local_col, a->sched_local_col);
+    copy_out(p->sched_remote_col.empty() ? p->remote_col : p->sched_remote_col, a->sched_remote_col);
     for (size_t i = 0; i < p->items.size(); ++i) {
         const WorkItem &it = p->items[i];
         if (a->item_row) a->item_row[i] = it.row;

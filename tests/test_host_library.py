@@ -47,11 +47,17 @@ def _compare_with_oracle(row_ptr, col, parts, p, bounds, **opts):
     return got, info
 
 
+def _source_class(x):
+    return ((x.astype(np.uint64) * np.uint64(0x9E3779B1)) & np.uint64(0xFFFFFFFF)) >> np.uint64(29)
+
+
 def _check_schedule(got, info):
     """Several schedules are valid; check that this one covers every neighbour exactly once,
-    cuts rows only at multiples of ps * dist, and uses each scratch slot once."""
+    keeps items within one row and within ps * dist neighbours per list, uses each scratch slot
+    once, walks a per-row permutation of the canonical columns, and -- for rows regrouped by
+    source class -- gives every item a single class equal to the XCD its workgroup lands on."""
     n_own = info.n_own
-    lrp, rrp = got["local_row_ptr"], got["remote_row_ptr"]
+    lrp, rrp = got["local_row_ptr"].astype(np.int64), got["remote_row_ptr"].astype(np.int64)
     deg = np.diff(lrp) + np.diff(rrp)
     seen_rows = np.zeros(n_own, dtype=np.int64)
     np.add.at(seen_rows, got["short_rows"], 1)
@@ -59,23 +65,26 @@ def _check_schedule(got, info):
         assert np.all(deg[got["short_rows"]] <= info.short_max)
         assert np.all(np.diff(deg[got["short_rows"]]) <= 0)            # longest first
     run = info.ps * info.dist
-    cover_l = np.zeros(n_own, dtype=np.int64)
-    cover_r = np.zeros(n_own, dtype=np.int64)
-    rows = got["item_row"]
-    np.add.at(cover_l, rows, got["item_lend"] - got["item_lbeg"])
-    np.add.at(cover_r, rows, got["item_rend"] - got["item_rbeg"])
+    valid = got["item_row"] >= 0                                       # the rest is padding
+    pos = np.nonzero(valid)[0]
+    rows = got["item_row"][valid].astype(np.int64)
+    lbeg, lend = got["item_lbeg"][valid].astype(np.int64), got["item_lend"][valid].astype(np.int64)
+    rbeg, rend = got["item_rbeg"][valid].astype(np.int64), got["item_rend"][valid].astype(np.int64)
+    slots = got["item_slot"][valid]
+    assert np.all(got["item_slot"][~valid] == -1)
     item_rows = np.unique(rows)
     seen_rows[item_rows] += 1
     assert np.all(seen_rows == 1)                                      # every row in exactly one bin
-    assert np.array_equal(cover_l[item_rows], np.diff(lrp)[item_rows])
-    assert np.array_equal(cover_r[item_rows], np.diff(rrp)[item_rows])
-    empty_l, empty_r = got["item_lbeg"] == got["item_lend"], got["item_rbeg"] == got["item_rend"]
-    assert np.all(((got["item_lbeg"] - lrp[rows]) % run == 0) | empty_l)   # cuts at partition-run boundaries
-    assert np.all(((got["item_rbeg"] - rrp[rows]) % run == 0) | empty_r)
-    assert np.all(got["item_lend"] - got["item_lbeg"] <= run) and np.all(got["item_rend"] - got["item_rbeg"] <= run)
-    assert np.all(got["item_lbeg"] >= lrp[rows]) and np.all(got["item_lend"] <= lrp[rows + 1])
-    assert np.all(got["item_rbeg"] >= rrp[rows]) and np.all(got["item_rend"] <= rrp[rows + 1])
-    slots = got["item_slot"]
+    for beg, end, rp in ((lbeg, lend, lrp), (rbeg, rend, rrp)):
+        assert np.all(end - beg <= run) and np.all(end >= beg)
+        assert np.all(beg >= rp[rows]) and np.all(end <= rp[rows + 1])  # inside the item's row
+        ne = end > beg
+        order = np.argsort(beg[ne], kind="stable")
+        b, e = beg[ne][order], end[ne][order]
+        assert np.all(e[:-1] <= b[1:])                                  # no neighbour twice
+        cover = np.zeros(n_own, dtype=np.int64)
+        np.add.at(cover, rows, end - beg)
+        assert np.array_equal(cover[item_rows], np.diff(rp)[item_rows])   # no neighbour missed
     whole = slots < 0
     counts = np.bincount(rows, minlength=n_own)
     assert np.all(counts[rows[whole]] == 1) and np.all(counts[rows[~whole]] > 1)
@@ -83,6 +92,24 @@ def _check_schedule(got, info):
     assert info.n_split_rows == np.unique(rows[~whole]).size
     assert info.n_groups_local == int(np.sum(-(-np.diff(lrp) // info.ps)))
     assert info.n_groups_remote == int(np.sum(-(-np.diff(rrp) // info.ps)))
+    # the kernel's column order is the canonical one permuted inside each row
+    for canon, sched, rp in ((got["local_col"], got["sched_local_col"], lrp), (got["remote_col"], got["sched_remote_col"], rrp)):
+        row_of = np.repeat(np.arange(n_own, dtype=np.int64), np.diff(rp))
+        big = np.int64(1) << 32
+        assert np.array_equal(np.sort(row_of * big + canon), np.sort(row_of * big + sched))
+    if info.xcd_min_deg > 0:
+        assert got["item_row"].size % 32 == 0                           # 8 XCDs x 4 items per workgroup
+        regrouped = deg[rows] >= info.xcd_min_deg
+        xcd = (pos // 4) % 8
+        for i in np.nonzero(regrouped)[0][:4000]:
+            cols = np.concatenate([got["sched_local_col"][lbeg[i]:lend[i]], got["sched_remote_col"][rbeg[i]:rend[i]]])
+            assert cols.size and np.all(_source_class(cols) == xcd[i])
+        light = ~regrouped & whole
+        assert np.all(counts[rows[light]] == 1)
+    else:
+        assert np.array_equal(got["sched_local_col"], got["local_col"])
+        assert np.array_equal(got["sched_remote_col"], got["remote_col"])
+        assert np.all(valid)
 
 
 def test_partition_matches_hand_written_fixture():
@@ -101,15 +128,17 @@ def test_partition_matches_hand_written_fixture():
             assert got[f"grp_{kind}_end"].tolist() == g["end"]
 
 
+@pytest.mark.parametrize("xcd_min_deg", [-1, 1, 24, 300])
 @pytest.mark.parametrize("parts,ps,dist,short_max", [(1, 0, 0, 0), (4, 32, 16, 16), (4, 2, 1, -1), (3, 7, 3, 5),
                                                      (8, 64, 1, 40), (2, 1, 1, 1)])
-def test_partition_bit_exact_against_oracle(parts, ps, dist, short_max):
+def test_partition_bit_exact_against_oracle(parts, ps, dist, short_max, xcd_min_deg):
     rng = np.random.default_rng(parts * 100 + ps)
     row_ptr, col = inputs.rmat_graph(12, 50000, 0.57, 0.19, 0.19, 0.05, rng)
     n = row_ptr.size - 1
     bounds = inputs.equal_node_bounds(n, parts)
     for p in range(parts):
-        _compare_with_oracle(row_ptr, col, parts, p, bounds, ps=ps, dist=dist, short_max=short_max)
+        _compare_with_oracle(row_ptr, col, parts, p, bounds, ps=ps, dist=dist, short_max=short_max,
+                             xcd_min_deg=xcd_min_deg)
 
 
 def test_partition_with_self_loops_duplicates_and_empty_ranges():
