@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # workload name -> bytes per launch of the dominant aggregation kernel (None = not measured)
 MEASURED_TRAFFIC_BYTES = {
     "cfg2_rmat20_gcn64_p4": 2270318481,          # profiles/aggregate_cfg2_rmat20_gcn64.md
-    "cfg4_powerlaw233k_gcn602": 248783651257,    # profiles/aggregate_cfg4_powerlaw233k_gcn602.md
+    "cfg4_powerlaw233k_gcn602": None,            # re-measured below once the slab passes are profiled
     "cfg5_rmat2.4M_gcn2layer_p8": 40717611000,   # profiles/aggregate_cfg5_rmat2.4M_gcn_dim100_dim256.md (layer 1, dim 256)
 }
 
@@ -42,11 +42,22 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def to_dev(a, dev):
+def to_dev(a, dev, pad_rows_to_bytes=0):
+    """Host array -> device tensor.  With pad_rows_to_bytes the rows are laid out with a leading
+    dimension rounded up so that every row starts on that byte boundary (the API takes ld_x)."""
     import torch
     if a.dtype == np.uint16:
-        return torch.from_numpy(a.view(np.int16).copy()).to(dev).view(torch.bfloat16)
-    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        t = torch.from_numpy(a.view(np.int16).copy()).to(dev).view(torch.bfloat16)
+    else:
+        t = torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    if pad_rows_to_bytes and t.dim() == 2:
+        per = pad_rows_to_bytes // t.element_size()
+        ld = (t.shape[1] + per - 1) // per * per
+        if ld != t.shape[1]:
+            buf = torch.zeros((t.shape[0], ld), dtype=t.dtype, device=dev)
+            buf[:, :t.shape[1]].copy_(t)
+            return buf[:, :t.shape[1]]
+    return t
 
 
 def gather_model_bytes(nnz, n_own, dim, elem_bytes, gcn):
@@ -110,7 +121,10 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
     for li, layer in enumerate(w.layers):
         d_in = layer.dims[0]
         if li == 0:
-            xl, xh = to_dev(x_local_np, dev), (to_dev(x_halo_np, dev) if halo_gid.size else None)
+            # rows that are not a multiple of 16 bytes are laid out on 128-byte lines so that the
+            # kernel can use 16-byte loads (config 4: 602 floats -> leading dimension 608)
+            pad = 128 if (d_in * esz) % 16 else 0
+            xl, xh = to_dev(x_local_np, dev, pad), (to_dev(x_halo_np, dev, pad) if halo_gid.size else None)
             lesz = esz
         else:
             # layer 2 reads layer 1's output for owned rows; halo rows are a seeded stand-in for

@@ -36,6 +36,7 @@ struct AggArgs {
     float *out, *scratch;
     int64_t ld_x, ld_out, scratch_ld;
     int32_t nvec;            // vectors of VEC elements per row (dim / VEC)
+    int32_t slab_vecs;       // vectors per column slab; blockIdx.y selects the slab (= nvec: one slab)
     int32_t n_items, n_item_blocks, n_short;
     int32_t ps;
     int32_t gcn;             // 1: symmetric normalisation, 0: plain sum
@@ -118,7 +119,7 @@ struct Acc {
 
 // Final value of an owned row from its neighbour sum: adds the self term and the row factor.
 template <class K>
-__device__ __forceinline__ void write_final(const AggArgs &a, const Acc<K> &acc, int32_t row, int lis)
+__device__ __forceinline__ void write_final(const AggArgs &a, const Acc<K> &acc, int32_t row, int lis, int vend)
 {
     const typename K::elem *xs = static_cast<const typename K::elem *>(a.x_local) + static_cast<int64_t>(row) * a.ld_x;
     float *o = a.out + static_cast<int64_t>(row) * a.ld_out;
@@ -127,7 +128,7 @@ __device__ __forceinline__ void write_final(const AggArgs &a, const Acc<K> &acc,
 #pragma unroll
     for (int c = 0; c < K::CH; ++c) {
         const int vi = c * K::LPR + lis;
-        if (vi < a.nvec) {
+        if (vi < vend) {
             float xv[K::VEC], r[K::VEC];
             unpack<K::BF16, K::VEC>(*reinterpret_cast<const typename K::raw *>(xs + static_cast<int64_t>(vi) * K::VEC), xv);
 #pragma unroll
@@ -138,13 +139,13 @@ __device__ __forceinline__ void write_final(const AggArgs &a, const Acc<K> &acc,
 }
 
 template <class K>
-__device__ __forceinline__ void write_partial(const AggArgs &a, const Acc<K> &acc, int32_t slot, int lis)
+__device__ __forceinline__ void write_partial(const AggArgs &a, const Acc<K> &acc, int32_t slot, int lis, int vend)
 {
     float *o = a.scratch + static_cast<int64_t>(slot) * a.scratch_ld;
 #pragma unroll
     for (int c = 0; c < K::CH; ++c) {
         const int vi = c * K::LPR + lis;
-        if (vi < a.nvec) store_vec<K::VEC>(o + static_cast<int64_t>(vi) * K::VEC, acc.v[c], true);
+        if (vi < vend) store_vec<K::VEC>(o + static_cast<int64_t>(vi) * K::VEC, acc.v[c], true);
     }
 }
 
@@ -303,7 +304,9 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int sub = lane / K::LPR;      // which neighbour row of a load instruction
-    const int lis = lane % K::LPR;      // lane inside the sub-wave = which vector of the row
+    // first vector of the row this lane owns: lane inside the sub-wave, shifted to the column slab
+    const int lis = lane % K::LPR + static_cast<int>(blockIdx.y) * a.slab_vecs;
+    const int vend = min(a.nvec, (static_cast<int>(blockIdx.y) + 1) * a.slab_vecs);   // end of the slab
     const typename K::elem *xl = static_cast<const typename K::elem *>(a.x_local);
     const typename K::elem *xh = static_cast<const typename K::elem *>(a.x_halo);
     const bool gcn = a.gcn != 0;
@@ -332,12 +335,12 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
             const int len_l = min(ps, n_l - g * ps), len_r = min(ps, n_r - g * ps);
             if constexpr (LDSH) {
                 uint4 (*stage)[kWave] = stage_all[wave];
-                if (len_r > 0) stage_halo_rows<K>(stage, xh, a.ld_x, idx_r, len_r, 0, sub, lis, a.nvec);
-                if (len_l > 0) accumulate_partition<K>(acc, xl, a.ld_x, idx_l, w_l, len_l, sub, lis, a.nvec);
-                if (len_r > 0) consume_staged_rows<K>(acc, stage, xh, a.ld_x, idx_r, w_r, len_r, sub, lis, a.nvec, lane);
+                if (len_r > 0) stage_halo_rows<K>(stage, xh, a.ld_x, idx_r, len_r, 0, sub, lis, vend);
+                if (len_l > 0) accumulate_partition<K>(acc, xl, a.ld_x, idx_l, w_l, len_l, sub, lis, vend);
+                if (len_r > 0) consume_staged_rows<K>(acc, stage, xh, a.ld_x, idx_r, w_r, len_r, sub, lis, vend, lane);
             } else {
-                if (len_l > 0) accumulate_partition<K>(acc, xl, a.ld_x, idx_l, w_l, len_l, sub, lis, a.nvec);
-                if (len_r > 0) accumulate_partition<K>(acc, xh, a.ld_x, idx_r, w_r, len_r, sub, lis, a.nvec);
+                if (len_l > 0) accumulate_partition<K>(acc, xl, a.ld_x, idx_l, w_l, len_l, sub, lis, vend);
+                if (len_r > 0) accumulate_partition<K>(acc, xh, a.ld_x, idx_r, w_r, len_r, sub, lis, vend);
             }
             idx_l = nidx_l; w_l = nw_l; idx_r = nidx_r; w_r = nw_r;
         }
@@ -349,8 +352,8 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
 #pragma unroll
                 for (int e = 0; e < K::VEC; ++e) acc.v[c][e] += __shfl_xor(acc.v[c][e], off);
         if (sub == 0) {
-            if (it.slot < 0) write_final<K>(a, acc, it.row, lis);
-            else write_partial<K>(a, acc, it.slot, lis);
+            if (it.slot < 0) write_final<K>(a, acc, it.row, lis, vend);
+            else write_partial<K>(a, acc, it.slot, lis, vend);
         }
     } else {
         // ---- short rows: one per sub-wave -----------------------------------------------------
@@ -359,10 +362,10 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
         if (s_id >= a.n_short) return;
         const int32_t row = a.short_rows[s_id];
         accumulate_list<K>(acc, xl, a.ld_x, a.local_col, a.dinv_own, a.local_row_ptr[row], a.local_row_ptr[row + 1],
-                           gcn, lis, a.nvec);
+                           gcn, lis, vend);
         accumulate_list<K>(acc, xh, a.ld_x, a.remote_col, a.dinv_halo, a.remote_row_ptr[row], a.remote_row_ptr[row + 1],
-                           gcn, lis, a.nvec);
-        write_final<K>(a, acc, row, lis);
+                           gcn, lis, vend);
+        write_final<K>(a, acc, row, lis, vend);
     }
 }
 
@@ -411,21 +414,21 @@ __global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_row
 }
 
 template <class K>
-hipError_t launch_cfg(const AggArgs &a, int grid, hipStream_t stream, bool lds_halo)
+hipError_t launch_cfg(const AggArgs &a, dim3 grid, hipStream_t stream, bool lds_halo)
 {
     if constexpr (K::CH == 1 && sizeof(typename K::raw) == 16) {
         if (lds_halo) {
-            hipLaunchKernelGGL((aggregate_kernel<K, true>), dim3(grid), dim3(kBlock), 0, stream, a);
+            hipLaunchKernelGGL((aggregate_kernel<K, true>), grid, dim3(kBlock), 0, stream, a);
             return hipGetLastError();
         }
     }
-    hipLaunchKernelGGL((aggregate_kernel<K, false>), dim3(grid), dim3(kBlock), 0, stream, a);
+    hipLaunchKernelGGL((aggregate_kernel<K, false>), grid, dim3(kBlock), 0, stream, a);
     return hipGetLastError();
 }
 
 // LPR = smallest power of two >= nvec (at least 4, at most 64); CH = chunks per lane.
 template <bool BF16, int VEC>
-hipError_t dispatch_shape(const AggArgs &a, int grid, hipStream_t stream, int lpr, int ch, bool lds)
+hipError_t dispatch_shape(const AggArgs &a, dim3 grid, hipStream_t stream, int lpr, int ch, bool lds)
 {
     if (lpr == 4) return launch_cfg<Cfg<BF16, VEC, 4, 1>>(a, grid, stream, lds);
     if (lpr == 8) return launch_cfg<Cfg<BF16, VEC, 8, 1>>(a, grid, stream, lds);
@@ -457,11 +460,34 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
         if (dim % c == 0 && ld_x % c == 0 && aligned(x_local, bytes) && aligned(xh, bytes)) { vec = c; break; }
     }
     const int nvec = dim / vec;
+    // Column slabs: when one XCD's share of the table rows does not fit its L2 at full width, the
+    // launch walks the feature dimension slab by slab (grid.y), all work items of slab 0 first,
+    // so that what stays in L2 between two uses of a table row is a slab of it, not the whole
+    // row.  Costs one more pass over the ids per slab; output columns of different slabs are
+    // disjoint, so nothing has to be combined.
+    int slab_vecs = nvec;
+    {
+        const int64_t opt = option_col_slab_bytes();
+        const int64_t vec_bytes = static_cast<int64_t>(vec) * static_cast<int64_t>(esz);
+        int64_t slab_bytes = 0;
+        if (opt == 0) {
+            // automatic: measured on MI355X, 512-byte slabs pay (1.1-1.3x) when rows are at least
+            // two slabs wide and one XCD's share of the table rows, at slab width, stays within a
+            // few times its 4 MB L2; narrower slabs or larger tables lose to the extra passes
+            const int64_t table_rows = p->n_own + static_cast<int64_t>(p->halo_gid.size());
+            const int64_t class_rows = (p->xcd_min_deg > 0 ? table_rows / kXcd : table_rows) + 1;
+            if (static_cast<int64_t>(dim) * static_cast<int64_t>(esz) >= 1024 && class_rows * 512 <= (16 << 20)) slab_bytes = 512;
+        } else if (opt >= 64) {
+            slab_bytes = opt;
+        }
+        if (slab_bytes > 0 && slab_bytes % vec_bytes == 0 && slab_bytes / vec_bytes < nvec) slab_vecs = static_cast<int>(slab_bytes / vec_bytes);
+    }
+    const int n_slabs = (nvec + slab_vecs - 1) / slab_vecs;
     // a lane holds at most 8 chunks; wider rows would need a column loop
-    if (nvec > 64 * 8) return fail(MGG_ERR_UNSUPPORTED, "dim %d too wide for %d-element vectors (max %d)", dim, vec, 64 * 8 * vec);
+    if (slab_vecs > 64 * 8) return fail(MGG_ERR_UNSUPPORTED, "dim %d too wide for %d-element vectors (max %d)", dim, vec, 64 * 8 * vec);
     int lpr = 4;
-    while (lpr < nvec && lpr < 64) lpr <<= 1;
-    const int ch = (nvec + 63) / 64;
+    while (lpr < slab_vecs && lpr < 64) lpr <<= 1;
+    const int ch = (slab_vecs + 63) / 64;
 
     // scratch rows for the partial sums of split rows
     if (p->n_split_items > 0) {
@@ -484,6 +510,7 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
     a.out = out; a.scratch = p->d.scratch;
     a.ld_x = ld_x; a.ld_out = ld_out; a.scratch_ld = p->d.scratch_ld;
     a.nvec = nvec;
+    a.slab_vecs = slab_vecs;
     a.n_items = static_cast<int32_t>(p->items.size());
     a.n_item_blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
     a.n_short = static_cast<int32_t>(p->short_rows.size());
@@ -495,9 +522,11 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
 
     const int npw = 64 / lpr;
     const int short_waves = (a.n_short + npw - 1) / npw;
-    const int grid = a.n_item_blocks + (short_waves + kWavesPerBlock - 1) / kWavesPerBlock;
+    int grid_x = a.n_item_blocks + (short_waves + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (n_slabs > 1) grid_x = (grid_x + kXcd - 1) / kXcd * kXcd;   // keeps workgroup x on XCD x mod 8 in every slab
+    const dim3 grid(static_cast<unsigned>(grid_x), static_cast<unsigned>(n_slabs));
     const bool lds = option_lds_halo() != 0 && !p->halo_gid.empty();
-    if (grid > 0) {
+    if (grid_x > 0) {
         hipError_t e;
         if (bf16) {
             if (vec == 8) e = dispatch_shape<true, 8>(a, grid, stream, lpr, ch, lds);

@@ -8,8 +8,10 @@ namespace mgg {
 
 static std::atomic<int32_t> g_xcd_remap{0};
 static std::atomic<int32_t> g_lds_halo{0};
+static std::atomic<int32_t> g_col_slab_bytes{0};
 int32_t option_xcd_remap() { return g_xcd_remap.load(); }
 int32_t option_lds_halo() { return g_lds_halo.load(); }
+int32_t option_col_slab_bytes() { return g_col_slab_bytes.load(); }
 
 static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline bool dtype_ok(mgg_dtype_t t) { return t == MGG_F32 || t == MGG_BF16; }
@@ -143,7 +145,14 @@ mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t 
 
 mgg_status_t mgg_set_option(const char *key, int32_t value)
 {
-    if (!key || (value != 0 && value != 1)) return fail(MGG_ERR_INVALID_ARG, "option value must be 0 or 1");
+    if (!key) return fail(MGG_ERR_INVALID_ARG, "key is NULL");
+    if (!std::strcmp(key, "col_slab_bytes")) {
+        // 0: automatic, 1: off, otherwise a power of two between 64 and 4096
+        if (value != 0 && value != 1 && (value < 64 || value > 4096 || (value & (value - 1)))) return fail(MGG_ERR_INVALID_ARG, "col_slab_bytes must be 0, 1 or a power of two in [64, 4096]");
+        g_col_slab_bytes = value;
+        return MGG_OK;
+    }
+    if (value != 0 && value != 1) return fail(MGG_ERR_INVALID_ARG, "option value must be 0 or 1");
     if (!std::strcmp(key, "xcd_remap")) { g_xcd_remap = value; return MGG_OK; }
     if (!std::strcmp(key, "lds_halo")) { g_lds_halo = value; return MGG_OK; }
     return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
@@ -154,6 +163,7 @@ mgg_status_t mgg_get_option(const char *key, int32_t *value)
     if (!key || !value) return fail(MGG_ERR_INVALID_ARG, "NULL argument");
     if (!std::strcmp(key, "xcd_remap")) { *value = g_xcd_remap; return MGG_OK; }
     if (!std::strcmp(key, "lds_halo")) { *value = g_lds_halo; return MGG_OK; }
+    if (!std::strcmp(key, "col_slab_bytes")) { *value = g_col_slab_bytes; return MGG_OK; }
     return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
 }
 

@@ -227,6 +227,27 @@ def test_lds_staged_halo_rows_give_the_same_answer(lds_halo, dim, bf16, build):
         check_aggregate(row_ptr, col, 4, p, bounds, x, mode, build=build, what=f"lds dim {dim} {build} part {p}")
 
 
+@pytest.mark.parametrize("slab_bytes", [64, 128, 256, 1024])
+@pytest.mark.parametrize("dim,bf16", [(64, False), (100, False), (602, False), (608, False), (47, False), (128, True), (520, True), (130, True)])
+def test_column_slab_passes_give_the_same_answer(slab_bytes, dim, bf16):
+    """Walking the feature dimension slab by slab changes which bytes sit in L2, not the value."""
+    binding.mgg_set_option("col_slab_bytes", slab_bytes)
+    try:
+        row_ptr, col, rng = small_rmat(seed=500 + dim)
+        n = row_ptr.size - 1
+        x = rng.standard_normal((n, dim)).astype(np.float32)
+        if bf16:
+            x = inputs.to_bf16_bits(x)
+        bounds = inputs.equal_node_bounds(n, 4)
+        check_aggregate(row_ptr, col, 4, 0, bounds, x, "gcn", build=dict(xcd_min_deg=64), what=f"slab {slab_bytes} dim {dim}")
+        check_aggregate(row_ptr, col, 4, 2, bounds, x, "gin", build=dict(xcd_min_deg=-1, dist=2), what=f"slab {slab_bytes} dim {dim} gin")
+        binding.mgg_set_option("lds_halo", 1)
+        check_aggregate(row_ptr, col, 4, 1, bounds, x, "gcn", what=f"slab {slab_bytes} dim {dim} lds")
+    finally:
+        binding.mgg_set_option("col_slab_bytes", 0)
+        binding.mgg_set_option("lds_halo", 0)
+
+
 # ----------------------------------------------------------------------------- update
 def update_bound(a64, w64, k, bf16):
     s = np.abs(a64) @ np.abs(w64)

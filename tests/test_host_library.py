@@ -222,3 +222,9 @@ def test_options_round_trip():
         binding.mgg_set_option(key, 1 - old)
         assert binding.mgg_get_option(key) == 1 - old
         binding.mgg_set_option(key, old)
+    assert binding.mgg_get_option("col_slab_bytes") == 0
+    for v in (1, 64, 128, 4096, 0):
+        binding.mgg_set_option("col_slab_bytes", v)
+        assert binding.mgg_get_option("col_slab_bytes") == v
+    for bad in (-1, 3, 96, 8192):
+        assert _status(binding.mgg_set_option, "col_slab_bytes", bad) == binding.ERR_INVALID_ARG
