@@ -95,6 +95,52 @@ def cpu_baseline_leg(w, layer, x_local_np, x_halo_np, halo_gid, n_own, cpu_budge
                       f"{sample_edges} edges, {cpu_s:.1f}s"}
 
 
+ABLATIONS = [
+    # name, build options, run-time options -- one-GPU counterparts of the paper's kernel ablations
+    ("default", {}, {}),
+    ("no neighbour partitioning (a whole row per wavefront, section 7.2 'NP')", {"ps": 64, "dist": 1024, "xcd_min_deg": -1}, {}),
+    ("no interleaving (local and remote lists in two launches, section 7.2 'WI')", {}, {"split_phases": 1}),
+    ("no XCD-aware schedule", {"xcd_min_deg": -1}, {}),
+    ("no short-row bin", {"short_max": -1}, {}),
+    ("halo rows staged through LDS", {}, {"lds_halo": 1}),
+    ("no column slabs", {}, {"col_slab_bytes": 1}),
+]
+
+
+def run_ablations(cfg: int, iters: int = 20):
+    """Aggregation time of layer 0 under each variant; returns a list of dicts."""
+    import torch
+    from paper_2209_06800_amd import binding, inputs
+    dev = "cuda:0"
+    w = inputs.config(cfg)
+    layer = w.layers[0]
+    esz = 2 if w.dtype == "bf16" else 4
+    pad = 128 if (w.dim * esz) % 16 else 0
+    rows = []
+    base_ms = None
+    for name, build, opts in ABLATIONS:
+        part = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds, **build)
+        hg = part.export()["halo_gid"]
+        xl = to_dev(w.x[w.lb:w.ub], dev, pad)
+        xh = to_dev(w.x[hg], dev, pad) if hg.size else None
+        out = torch.empty((int(part.info.n_own), w.dim), dtype=torch.float32, device=dev)
+        for k, v in opts.items():
+            binding.mgg_set_option(k, v)
+        try:
+            ms = min(binding.mgg_time_aggregate(part, layer.mode, xl, xh, out, eps=layer.eps, iters=iters) for _ in range(3))
+        finally:
+            for k in opts:
+                binding.mgg_set_option(k, 0)
+        nnz = int(part.info.nnz_local + part.info.nnz_remote)
+        base_ms = ms if base_ms is None else base_ms
+        rows.append({"variant": name, "agg_ms": round(ms, 4), "gedges_per_s": round(nnz / ms / 1e6, 3),
+                     "slowdown_vs_default": round(ms / base_ms, 3)})
+        log(f"[ablation] {name}: {ms:.4f} ms  {nnz / ms / 1e6:.2f} GEdges/s  x{ms / base_ms:.3f}")
+        part.destroy()
+        del xl, xh, out
+    return rows
+
+
 def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 20.0, calibrate_copy: bool = False):
     import torch
     from paper_2209_06800_amd import binding, inputs
@@ -247,6 +293,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--verify", action="store_true", help="compare sampled rows with the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the cpu_baseline leg (0 = skip it)")
+    ap.add_argument("--ablations", action="store_true",
+                    help="time the aggregation of layer 0 with neighbour partitioning, interleaving, the XCD-aware "
+                         "schedule, the short-row bin, LDS staging and column slabs switched one at a time, and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a 1 GiB device copy three times (reference for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -254,6 +303,9 @@ def main():
         print("bench.py measures one GPU's share on one MI355X; multi-GPU runs are not part of this build "
               "(no collectives, no second GPU). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    if args.ablations:
+        print(json.dumps({"workload_config": args.config, "ablations": run_ablations(args.config)}), flush=True)
+        return
     res = run(args.config, args.steps, args.warmup, args.verify, args.cpu_seconds, args.calibrate_copy)
     print(json.dumps(res), flush=True)
 

@@ -197,6 +197,8 @@ mgg_status_t mgg_split_edge_balanced(int64_t num_nodes, const int64_t *row_ptr, 
 /* Run-time switches for experiments (ablations of section 7.2's kind).  Known keys:
  *   "xcd_remap"   0/1  contiguous chunks of work items per XCD            (default 1)
  *   "lds_halo"    0/1  stage halo rows through LDS ahead of accumulation  (default 0)
+ *   "split_phases" 0/1 aggregate the local lists and the remote lists in two launches, the
+ *                      second adding to the first (no interleaving; default 0)
  *   "col_slab_bytes"   0 = automatic (default), 1 = off, or a power of two in [64, 4096]:
  *                      bytes of an embedding row handled per pass over the work items
  * Unknown key or bad value -> MGG_ERR_INVALID_ARG.  Not thread-safe against running calls. */

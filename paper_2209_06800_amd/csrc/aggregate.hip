@@ -42,6 +42,8 @@ struct AggArgs {
     int32_t gcn;             // 1: symmetric normalisation, 0: plain sum
     float self_w;            // GIN: 1 + eps
     int32_t out_vec_ok;      // out rows allow VEC-wide stores
+    int32_t phase;           // 0: local and remote lists in one launch; 1: local lists (+ self term) only;
+                             // 2: remote lists only, added to what phase 1 left in out
 };
 
 // ---- element access ---------------------------------------------------------------------
@@ -131,8 +133,13 @@ __device__ __forceinline__ void write_final(const AggArgs &a, const Acc<K> &acc,
         if (vi < vend) {
             float xv[K::VEC], r[K::VEC];
             unpack<K::BF16, K::VEC>(*reinterpret_cast<const typename K::raw *>(xs + static_cast<int64_t>(vi) * K::VEC), xv);
+            if (a.phase == 2) {                 // second of two launches: add to the first one's result
 #pragma unroll
-            for (int e = 0; e < K::VEC; ++e) r[e] = dv * (acc.v[c][e] + ws * xv[e]);
+                for (int e = 0; e < K::VEC; ++e) r[e] = o[static_cast<int64_t>(vi) * K::VEC + e] + dv * acc.v[c][e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < K::VEC; ++e) r[e] = dv * (acc.v[c][e] + ws * xv[e]);
+            }
             store_vec<K::VEC>(o + static_cast<int64_t>(vi) * K::VEC, r, a.out_vec_ok);
         }
     }
@@ -320,7 +327,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
         const WorkItem it = a.items[item_id];
         if (it.row < 0) return;                         // padding item
         const int ps = a.ps;
-        const int n_l = it.lend - it.lbeg, n_r = it.rend - it.rbeg;
+        const int n_l = a.phase == 2 ? 0 : it.lend - it.lbeg, n_r = a.phase == 1 ? 0 : it.rend - it.rbeg;
         const int g_l = (n_l + ps - 1) / ps, g_r = (n_r + ps - 1) / ps;
         const int g_n = g_l > g_r ? g_l : g_r;
         int idx_l, idx_r, nidx_l = 0, nidx_r = 0;
@@ -361,10 +368,12 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
         const int s_id = w_id * K::NPW + sub;
         if (s_id >= a.n_short) return;
         const int32_t row = a.short_rows[s_id];
-        accumulate_list<K>(acc, xl, a.ld_x, a.local_col, a.dinv_own, a.local_row_ptr[row], a.local_row_ptr[row + 1],
-                           gcn, lis, vend);
-        accumulate_list<K>(acc, xh, a.ld_x, a.remote_col, a.dinv_halo, a.remote_row_ptr[row], a.remote_row_ptr[row + 1],
-                           gcn, lis, vend);
+        if (a.phase != 2)
+            accumulate_list<K>(acc, xl, a.ld_x, a.local_col, a.dinv_own, a.local_row_ptr[row], a.local_row_ptr[row + 1],
+                               gcn, lis, vend);
+        if (a.phase != 1)
+            accumulate_list<K>(acc, xh, a.ld_x, a.remote_col, a.dinv_halo, a.remote_row_ptr[row], a.remote_row_ptr[row + 1],
+                               gcn, lis, vend);
         write_final<K>(a, acc, row, lis, vend);
     }
 }
@@ -376,7 +385,7 @@ template <bool BF16>
 __global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_rows, int32_t dim, const float *scratch,
                                                        int64_t scratch_ld, const void *x_local, int64_t ld_x,
                                                        const float *dinv_own, int32_t gcn, float self_w, float *out,
-                                                       int64_t ld_out)
+                                                       int64_t ld_out, int32_t phase)
 {
     __shared__ float part[kWavesPerBlock][kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -407,7 +416,8 @@ __global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_row
                 xv = __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k]) << 16);
             else
                 xv = static_cast<const float *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k];
-            out[static_cast<int64_t>(sr.row) * ld_out + k] = dv * (total + ws * xv);
+            float *o = out + static_cast<int64_t>(sr.row) * ld_out + k;
+            *o = phase == 2 ? *o + dv * total : dv * (total + ws * xv);
         }
         __syncthreads();
     }
@@ -520,35 +530,41 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
     const size_t out_bytes = (vec >= 4 ? 4 : vec) * sizeof(float);
     a.out_vec_ok = (ld_out % (vec >= 4 ? 4 : vec) == 0) && aligned(out, out_bytes);
 
-    const int npw = 64 / lpr;
-    const int short_waves = (a.n_short + npw - 1) / npw;
-    int grid_x = a.n_item_blocks + (short_waves + kWavesPerBlock - 1) / kWavesPerBlock;
-    if (n_slabs > 1) grid_x = (grid_x + kXcd - 1) / kXcd * kXcd;   // keeps workgroup x on XCD x mod 8 in every slab
-    const dim3 grid(static_cast<unsigned>(grid_x), static_cast<unsigned>(n_slabs));
-    const bool lds = option_lds_halo() != 0 && !p->halo_gid.empty();
-    if (grid_x > 0) {
-        hipError_t e;
-        if (bf16) {
-            if (vec == 8) e = dispatch_shape<true, 8>(a, grid, stream, lpr, ch, lds);
-            else if (vec == 2) e = dispatch_shape<true, 2>(a, grid, stream, lpr, ch, lds);
-            else e = dispatch_shape<true, 1>(a, grid, stream, lpr, ch, lds);
-        } else {
-            if (vec == 4) e = dispatch_shape<false, 4>(a, grid, stream, lpr, ch, lds);
-            else if (vec == 2) e = dispatch_shape<false, 2>(a, grid, stream, lpr, ch, lds);
-            else e = dispatch_shape<false, 1>(a, grid, stream, lpr, ch, lds);
+    // one launch for both neighbour lists (the default), or -- as the ablation of interleaving --
+    // the local lists first and the remote lists in a second launch that adds to the result
+    const bool two_phases = option_split_phases() != 0 && !p->halo_gid.empty();
+    for (int phase = two_phases ? 1 : 0; phase <= (two_phases ? 2 : 0); ++phase) {
+        a.phase = phase;
+        const int npw = 64 / lpr;
+        const int short_waves = (a.n_short + npw - 1) / npw;
+        int grid_x = a.n_item_blocks + (short_waves + kWavesPerBlock - 1) / kWavesPerBlock;
+        if (n_slabs > 1) grid_x = (grid_x + kXcd - 1) / kXcd * kXcd;   // keeps workgroup x on XCD x mod 8 in every slab
+        const dim3 grid(static_cast<unsigned>(grid_x), static_cast<unsigned>(n_slabs));
+        const bool lds = option_lds_halo() != 0 && !p->halo_gid.empty();
+        if (grid_x > 0) {
+            hipError_t e;
+            if (bf16) {
+                if (vec == 8) e = dispatch_shape<true, 8>(a, grid, stream, lpr, ch, lds);
+                else if (vec == 2) e = dispatch_shape<true, 2>(a, grid, stream, lpr, ch, lds);
+                else e = dispatch_shape<true, 1>(a, grid, stream, lpr, ch, lds);
+            } else {
+                if (vec == 4) e = dispatch_shape<false, 4>(a, grid, stream, lpr, ch, lds);
+                else if (vec == 2) e = dispatch_shape<false, 2>(a, grid, stream, lpr, ch, lds);
+                else e = dispatch_shape<false, 1>(a, grid, stream, lpr, ch, lds);
+            }
+            if (e != hipSuccess) return hip_fail(e, "aggregate kernel launch");
         }
-        if (e != hipSuccess) return hip_fail(e, "aggregate kernel launch");
-    }
-    const int32_t n_split = static_cast<int32_t>(p->split_rows.size());
-    if (n_split > 0) {
-        if (bf16)
-            hipLaunchKernelGGL(fixup_kernel<true>, dim3(n_split), dim3(kBlock), 0, stream, p->d.split_rows, dim,
-                               p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out);
-        else
-            hipLaunchKernelGGL(fixup_kernel<false>, dim3(n_split), dim3(kBlock), 0, stream, p->d.split_rows, dim,
-                               p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return hip_fail(e, "fix-up kernel launch");
+        const int32_t n_split = static_cast<int32_t>(p->split_rows.size());
+        if (n_split > 0) {
+            if (bf16)
+                hipLaunchKernelGGL(fixup_kernel<true>, dim3(n_split), dim3(kBlock), 0, stream, p->d.split_rows, dim,
+                                   p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out, a.phase);
+            else
+                hipLaunchKernelGGL(fixup_kernel<false>, dim3(n_split), dim3(kBlock), 0, stream, p->d.split_rows, dim,
+                                   p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out, a.phase);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return hip_fail(e, "fix-up kernel launch");
+        }
     }
     return MGG_OK;
 }

@@ -9,9 +9,11 @@ namespace mgg {
 static std::atomic<int32_t> g_xcd_remap{0};
 static std::atomic<int32_t> g_lds_halo{0};
 static std::atomic<int32_t> g_col_slab_bytes{0};
+static std::atomic<int32_t> g_split_phases{0};
 int32_t option_xcd_remap() { return g_xcd_remap.load(); }
 int32_t option_lds_halo() { return g_lds_halo.load(); }
 int32_t option_col_slab_bytes() { return g_col_slab_bytes.load(); }
+int32_t option_split_phases() { return g_split_phases.load(); }
 
 static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline bool dtype_ok(mgg_dtype_t t) { return t == MGG_F32 || t == MGG_BF16; }
@@ -155,6 +157,7 @@ mgg_status_t mgg_set_option(const char *key, int32_t value)
     if (value != 0 && value != 1) return fail(MGG_ERR_INVALID_ARG, "option value must be 0 or 1");
     if (!std::strcmp(key, "xcd_remap")) { g_xcd_remap = value; return MGG_OK; }
     if (!std::strcmp(key, "lds_halo")) { g_lds_halo = value; return MGG_OK; }
+    if (!std::strcmp(key, "split_phases")) { g_split_phases = value; return MGG_OK; }
     return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
 }
 
@@ -164,6 +167,7 @@ mgg_status_t mgg_get_option(const char *key, int32_t *value)
     if (!std::strcmp(key, "xcd_remap")) { *value = g_xcd_remap; return MGG_OK; }
     if (!std::strcmp(key, "lds_halo")) { *value = g_lds_halo; return MGG_OK; }
     if (!std::strcmp(key, "col_slab_bytes")) { *value = g_col_slab_bytes; return MGG_OK; }
+    if (!std::strcmp(key, "split_phases")) { *value = g_split_phases; return MGG_OK; }
     return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
 }
 

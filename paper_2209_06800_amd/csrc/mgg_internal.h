@@ -82,6 +82,7 @@ mgg_status_t hip_fail(hipError_t e, const char *what);
 int32_t option_xcd_remap();
 int32_t option_lds_halo();
 int32_t option_col_slab_bytes();
+int32_t option_split_phases();
 
 // kernels (aggregate.hip / update.hip)
 mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,

@@ -248,6 +248,24 @@ def test_column_slab_passes_give_the_same_answer(slab_bytes, dim, bf16):
         binding.mgg_set_option("lds_halo", 0)
 
 
+@pytest.mark.parametrize("dim,bf16,mode", [(64, False, "gcn"), (100, False, "gin"), (602, False, "gcn"), (128, True, "gin")])
+def test_local_and_remote_in_two_launches_give_the_same_answer(dim, bf16, mode):
+    """Ablation of interleaving (section 5.1): local lists first, remote lists added by a second launch."""
+    binding.mgg_set_option("split_phases", 1)
+    try:
+        row_ptr, col, rng = small_rmat(seed=700 + dim)
+        n = row_ptr.size - 1
+        x = rng.standard_normal((n, dim)).astype(np.float32)
+        if bf16:
+            x = inputs.to_bf16_bits(x)
+        bounds = inputs.equal_node_bounds(n, 4)
+        for p, build in ((0, dict()), (3, dict(ps=8, dist=2, xcd_min_deg=30)), (1, dict(xcd_min_deg=-1, short_max=-1))):
+            check_aggregate(row_ptr, col, 4, p, bounds, x, mode, eps=0.5, build=build, what=f"two launches dim {dim} part {p}")
+        check_aggregate(row_ptr, col, 1, 0, np.array([0, n]), x, mode, what="two launches, no halo")
+    finally:
+        binding.mgg_set_option("split_phases", 0)
+
+
 # ----------------------------------------------------------------------------- update
 def update_bound(a64, w64, k, bf16):
     s = np.abs(a64) @ np.abs(w64)
