@@ -49,7 +49,8 @@ typedef struct mgg_partition mgg_partition_t;   /* opaque, library-owned */
 
 /* Knobs of the partition build.  They are the paper's tuning parameters (section 6):
  * ps = neighbours per neighbour partition (1..64), dist = how many (local, remote)
- * partition pairs one wavefront work item covers (1..1024).  0 selects the default
+ * partition pairs one wavefront work item covers (1..1024), wpb = wavefronts per workgroup
+ * (the paper's warps per block).  0 selects the default
  * (ps 32, dist 16, short_max 16, xcd_min_deg 256).  Rows with at most short_max neighbours in total
  * are handled several per wavefront; short_max < 0 disables that bin. */
 typedef struct {
@@ -59,6 +60,8 @@ typedef struct {
     int32_t host_only;   /* nonzero: build on the host only, never touch the GPU (for
                             checks of the integer structures); device calls on such a
                             partition fail with MGG_ERR_INVALID_ARG */
+    int32_t wpb;         /* wavefronts (= work items) per workgroup of the aggregation kernel,
+                            1..16; 0 = default 4 */
     int32_t xcd_min_deg; /* rows with at least this many neighbours have their neighbour lists
                             regrouped into 8 source classes (a hash of the table row), one
                             per XCD, so each XCD's L2 serves one eighth of the table for
@@ -70,7 +73,7 @@ typedef struct {
     int64_t nnz_local, nnz_remote, num_halo;
     int32_t num_parts, part_id;
     int32_t ps, dist, short_max, on_device;
-    int32_t xcd_min_deg, reserved;
+    int32_t xcd_min_deg, wpb;
     int64_t n_groups_local, n_groups_remote;  /* neighbour partitions of the two CSRs        */
     int64_t n_short_rows;                     /* rows handled several per wavefront          */
     int64_t n_items;                          /* wavefront work items incl. padding items     */

@@ -39,7 +39,7 @@ class MggError(RuntimeError):
 
 class BuildOpts(C.Structure):
     _fields_ = [("ps", C.c_int32), ("dist", C.c_int32), ("short_max", C.c_int32), ("host_only", C.c_int32),
-                ("xcd_min_deg", C.c_int32)]
+                ("wpb", C.c_int32), ("xcd_min_deg", C.c_int32)]
 
 
 class PartitionInfo(C.Structure):
@@ -47,7 +47,7 @@ class PartitionInfo(C.Structure):
                 ("nnz_local", C.c_int64), ("nnz_remote", C.c_int64), ("num_halo", C.c_int64),
                 ("num_parts", C.c_int32), ("part_id", C.c_int32),
                 ("ps", C.c_int32), ("dist", C.c_int32), ("short_max", C.c_int32), ("on_device", C.c_int32),
-                ("xcd_min_deg", C.c_int32), ("reserved", C.c_int32),
+                ("xcd_min_deg", C.c_int32), ("wpb", C.c_int32),
                 ("n_groups_local", C.c_int64), ("n_groups_remote", C.c_int64),
                 ("n_short_rows", C.c_int64), ("n_items", C.c_int64),
                 ("n_split_rows", C.c_int64), ("n_split_items", C.c_int64)]
@@ -202,7 +202,7 @@ class Partition:
 
 def mgg_build_partition(row_ptr: np.ndarray, col_idx: np.ndarray, num_parts: int = 1, part_id: int = 0,
                         bounds: Optional[Sequence[int]] = None, *, ps: int = 0, dist: int = 0,
-                        short_max: int = 0, host_only: bool = False, xcd_min_deg: int = 0,
+                        short_max: int = 0, host_only: bool = False, xcd_min_deg: int = 0, wpb: int = 0,
                         num_nodes: Optional[int] = None) -> Partition:
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
@@ -210,7 +210,7 @@ def mgg_build_partition(row_ptr: np.ndarray, col_idx: np.ndarray, num_parts: int
     b = None if bounds is None else np.ascontiguousarray(bounds, dtype=np.int64)
     if b is not None and b.size != num_parts + 1:
         raise MggError(ERR_INVALID_ARG, "bounds must have num_parts + 1 entries")
-    opts = BuildOpts(ps, dist, short_max, int(host_only), xcd_min_deg)
+    opts = BuildOpts(ps, dist, short_max, int(host_only), wpb, xcd_min_deg)
     h = C.c_void_p()
     _check(lib().mgg_build_partition(n, _np_ptr(row_ptr), _np_ptr(col_idx) if col_idx.size else None,
                                      num_parts, part_id, _np_ptr(b), C.byref(opts), C.byref(h)))

@@ -24,8 +24,9 @@ namespace mgg {
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kWavesPerBlock = 4;
+constexpr int kWavesPerBlock = 4;                   // fix-up kernel, and the LDS stage of the staged variant
 constexpr int kBlock = kWave * kWavesPerBlock;
+constexpr int kMaxWpb = 16;                         // wavefronts per workgroup of the aggregation kernel
 
 struct AggArgs {
     const int32_t *local_row_ptr, *local_col, *remote_row_ptr, *remote_col;
@@ -305,11 +306,12 @@ __device__ __forceinline__ void consume_staged_rows(Acc<K> &acc, uint4 (*stage)[
 }
 
 template <class K, bool LDSH>
-__global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
+__global__ __launch_bounds__(kWave * kMaxWpb) void aggregate_kernel(const AggArgs a)
 {
     __shared__ uint4 stage_all[LDSH ? kWavesPerBlock : 1][LDSH ? kStageInstr : 1][LDSH ? kWave : 1];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
+    const int wpb = static_cast<int>(blockDim.x) / kWave;   // wavefronts (work items) per workgroup
     const int sub = lane / K::LPR;      // which neighbour row of a load instruction
     // first vector of the row this lane owns: lane inside the sub-wave, shifted to the column slab
     const int lis = lane % K::LPR + static_cast<int>(blockIdx.y) * a.slab_vecs;
@@ -322,7 +324,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
 
     if (static_cast<int>(blockIdx.x) < a.n_item_blocks) {
         // ---- one work item per wavefront ----------------------------------------------------
-        const int item_id = __builtin_amdgcn_readfirstlane(static_cast<int>(blockIdx.x) * kWavesPerBlock + wave);
+        const int item_id = __builtin_amdgcn_readfirstlane(static_cast<int>(blockIdx.x) * wpb + wave);
         if (item_id >= a.n_items) return;
         const WorkItem it = a.items[item_id];
         if (it.row < 0) return;                         // padding item
@@ -364,7 +366,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a)
         }
     } else {
         // ---- short rows: one per sub-wave -----------------------------------------------------
-        const int w_id = (static_cast<int>(blockIdx.x) - a.n_item_blocks) * kWavesPerBlock + wave;
+        const int w_id = (static_cast<int>(blockIdx.x) - a.n_item_blocks) * wpb + wave;
         const int s_id = w_id * K::NPW + sub;
         if (s_id >= a.n_short) return;
         const int32_t row = a.short_rows[s_id];
@@ -424,30 +426,30 @@ __global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_row
 }
 
 template <class K>
-hipError_t launch_cfg(const AggArgs &a, dim3 grid, hipStream_t stream, bool lds_halo)
+hipError_t launch_cfg(const AggArgs &a, dim3 grid, int wpb, hipStream_t stream, bool lds_halo)
 {
     if constexpr (K::CH == 1 && sizeof(typename K::raw) == 16) {
-        if (lds_halo) {
-            hipLaunchKernelGGL((aggregate_kernel<K, true>), grid, dim3(kBlock), 0, stream, a);
+        if (lds_halo && wpb <= kWavesPerBlock) {
+            hipLaunchKernelGGL((aggregate_kernel<K, true>), grid, dim3(kWave * wpb), 0, stream, a);
             return hipGetLastError();
         }
     }
-    hipLaunchKernelGGL((aggregate_kernel<K, false>), grid, dim3(kBlock), 0, stream, a);
+    hipLaunchKernelGGL((aggregate_kernel<K, false>), grid, dim3(kWave * wpb), 0, stream, a);
     return hipGetLastError();
 }
 
 // LPR = smallest power of two >= nvec (at least 4, at most 64); CH = chunks per lane.
 template <bool BF16, int VEC>
-hipError_t dispatch_shape(const AggArgs &a, dim3 grid, hipStream_t stream, int lpr, int ch, bool lds)
+hipError_t dispatch_shape(const AggArgs &a, dim3 grid, int wpb, hipStream_t stream, int lpr, int ch, bool lds)
 {
-    if (lpr == 4) return launch_cfg<Cfg<BF16, VEC, 4, 1>>(a, grid, stream, lds);
-    if (lpr == 8) return launch_cfg<Cfg<BF16, VEC, 8, 1>>(a, grid, stream, lds);
-    if (lpr == 16) return launch_cfg<Cfg<BF16, VEC, 16, 1>>(a, grid, stream, lds);
-    if (lpr == 32) return launch_cfg<Cfg<BF16, VEC, 32, 1>>(a, grid, stream, lds);
-    if (ch == 1) return launch_cfg<Cfg<BF16, VEC, 64, 1>>(a, grid, stream, lds);
-    if (ch == 2) return launch_cfg<Cfg<BF16, VEC, 64, 2>>(a, grid, stream, lds);
-    if (ch <= 4) return launch_cfg<Cfg<BF16, VEC, 64, 4>>(a, grid, stream, lds);
-    return launch_cfg<Cfg<BF16, VEC, 64, 8>>(a, grid, stream, lds);
+    if (lpr == 4) return launch_cfg<Cfg<BF16, VEC, 4, 1>>(a, grid, wpb, stream, lds);
+    if (lpr == 8) return launch_cfg<Cfg<BF16, VEC, 8, 1>>(a, grid, wpb, stream, lds);
+    if (lpr == 16) return launch_cfg<Cfg<BF16, VEC, 16, 1>>(a, grid, wpb, stream, lds);
+    if (lpr == 32) return launch_cfg<Cfg<BF16, VEC, 32, 1>>(a, grid, wpb, stream, lds);
+    if (ch == 1) return launch_cfg<Cfg<BF16, VEC, 64, 1>>(a, grid, wpb, stream, lds);
+    if (ch == 2) return launch_cfg<Cfg<BF16, VEC, 64, 2>>(a, grid, wpb, stream, lds);
+    if (ch <= 4) return launch_cfg<Cfg<BF16, VEC, 64, 4>>(a, grid, wpb, stream, lds);
+    return launch_cfg<Cfg<BF16, VEC, 64, 8>>(a, grid, wpb, stream, lds);
 }
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -522,7 +524,8 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
     a.nvec = nvec;
     a.slab_vecs = slab_vecs;
     a.n_items = static_cast<int32_t>(p->items.size());
-    a.n_item_blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int wpb = p->wpb;
+    a.n_item_blocks = (a.n_items + wpb - 1) / wpb;
     a.n_short = static_cast<int32_t>(p->short_rows.size());
     a.ps = p->ps;
     a.gcn = mode == MGG_AGG_GCN_SYM;
@@ -537,20 +540,20 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
         a.phase = phase;
         const int npw = 64 / lpr;
         const int short_waves = (a.n_short + npw - 1) / npw;
-        int grid_x = a.n_item_blocks + (short_waves + kWavesPerBlock - 1) / kWavesPerBlock;
+        int grid_x = a.n_item_blocks + (short_waves + wpb - 1) / wpb;
         if (n_slabs > 1) grid_x = (grid_x + kXcd - 1) / kXcd * kXcd;   // keeps workgroup x on XCD x mod 8 in every slab
         const dim3 grid(static_cast<unsigned>(grid_x), static_cast<unsigned>(n_slabs));
         const bool lds = option_lds_halo() != 0 && !p->halo_gid.empty();
         if (grid_x > 0) {
             hipError_t e;
             if (bf16) {
-                if (vec == 8) e = dispatch_shape<true, 8>(a, grid, stream, lpr, ch, lds);
-                else if (vec == 2) e = dispatch_shape<true, 2>(a, grid, stream, lpr, ch, lds);
-                else e = dispatch_shape<true, 1>(a, grid, stream, lpr, ch, lds);
+                if (vec == 8) e = dispatch_shape<true, 8>(a, grid, wpb, stream, lpr, ch, lds);
+                else if (vec == 2) e = dispatch_shape<true, 2>(a, grid, wpb, stream, lpr, ch, lds);
+                else e = dispatch_shape<true, 1>(a, grid, wpb, stream, lpr, ch, lds);
             } else {
-                if (vec == 4) e = dispatch_shape<false, 4>(a, grid, stream, lpr, ch, lds);
-                else if (vec == 2) e = dispatch_shape<false, 2>(a, grid, stream, lpr, ch, lds);
-                else e = dispatch_shape<false, 1>(a, grid, stream, lpr, ch, lds);
+                if (vec == 4) e = dispatch_shape<false, 4>(a, grid, wpb, stream, lpr, ch, lds);
+                else if (vec == 2) e = dispatch_shape<false, 2>(a, grid, wpb, stream, lpr, ch, lds);
+                else e = dispatch_shape<false, 1>(a, grid, wpb, stream, lpr, ch, lds);
             }
             if (e != hipSuccess) return hip_fail(e, "aggregate kernel launch");
         }

@@ -34,7 +34,7 @@ struct SplitRow {
 };
 
 constexpr int kXcd = 8;             // accelerator complex dies of an MI355X, each with its own L2
-constexpr int kItemsPerGroup = 4;   // work items (wavefronts) per workgroup of the aggregation kernel
+constexpr int kDefaultWpb = 4;      // work items (wavefronts) per workgroup of the aggregation kernel
 constexpr int kDefaultXcdMinDeg = 256;
 
 struct DeviceArrays {
@@ -53,7 +53,7 @@ struct DeviceArrays {
 struct mgg_partition {
     int64_t num_nodes = 0, lb = 0, ub = 0, n_own = 0;
     int32_t num_parts = 1, part_id = 0;
-    int32_t ps = 32, dist = 16, short_max = 16, xcd_min_deg = -1;
+    int32_t ps = 32, dist = 16, short_max = 16, xcd_min_deg = -1, wpb = 4;
     int device = -1;  // HIP device the arrays live on; -1 = host only
     std::vector<int32_t> local_row_ptr, local_col, remote_row_ptr, remote_col;
     std::vector<int32_t> sched_local_col, sched_remote_col;   // device order of the columns (empty: same as above)

@@ -113,17 +113,19 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
     if (num_nodes > INT32_MAX - 1) return fail(MGG_ERR_UNSUPPORTED, "more than 2^31-2 nodes");
     if (num_parts < 1 || part_id < 0 || part_id >= num_parts)
         return fail(MGG_ERR_INVALID_ARG, "part_id %d outside [0, %d)", part_id, num_parts);
-    int32_t ps = 32, dist = 16, short_max = 16, host_only = 0, xcd_min_deg = kDefaultXcdMinDeg;
+    int32_t ps = 32, dist = 16, short_max = 16, host_only = 0, xcd_min_deg = kDefaultXcdMinDeg, wpb = kDefaultWpb;
     if (opts) {
         if (opts->ps) ps = opts->ps;
         if (opts->dist) dist = opts->dist;
         if (opts->short_max) short_max = opts->short_max;
         host_only = opts->host_only;
         if (opts->xcd_min_deg) xcd_min_deg = opts->xcd_min_deg;
+        if (opts->wpb) wpb = opts->wpb;
     }
     if (ps < 1 || ps > 64) return fail(MGG_ERR_INVALID_ARG, "ps %d outside [1, 64]", ps);
     if (dist < 1 || dist > 1024) return fail(MGG_ERR_INVALID_ARG, "dist %d outside [1, 1024]", dist);
     if (short_max > 4096) return fail(MGG_ERR_INVALID_ARG, "short_max %d above 4096", short_max);
+    if (wpb < 1 || wpb > 16) return fail(MGG_ERR_INVALID_ARG, "wpb %d outside [1, 16]", wpb);
 
     // ---- validate the graph ------------------------------------------------------------
     if (row_ptr[0] != 0) return fail(MGG_ERR_BAD_GRAPH, "row_ptr[0] != 0");
@@ -156,7 +158,7 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
     try {
         p->num_nodes = num_nodes; p->lb = lb; p->ub = ub; p->n_own = n_own;
         p->num_parts = num_parts; p->part_id = part_id;
-        p->ps = ps; p->dist = dist; p->short_max = short_max; p->xcd_min_deg = xcd_min_deg;
+        p->ps = ps; p->dist = dist; p->short_max = short_max; p->xcd_min_deg = xcd_min_deg; p->wpb = wpb;
 
         // ---- pass 1: count local / remote per owned row, mark halo nodes -----------------
         std::vector<uint8_t> is_halo(static_cast<size_t>(num_nodes), 0);
@@ -301,16 +303,16 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
                 queue[c].push_back(it);
                 queue_work[c] += item_work(it);
             }
-            // launch order: workgroup b (four items) runs on XCD b mod kXcd; pad with empty items
+            // launch order: workgroup b (wpb items) runs on XCD b mod kXcd; pad with empty items
             size_t longest = 0;
             for (auto &q : queue) longest = std::max(longest, q.size());
-            longest = (longest + kItemsPerGroup - 1) / kItemsPerGroup * kItemsPerGroup;
+            longest = (longest + wpb - 1) / wpb * wpb;
             const WorkItem dummy{-1, 0, 0, 0, 0, -1, 0, 0};
             for (auto &q : queue) q.resize(longest, dummy);
             p->items.reserve(longest * kXcd);
-            for (size_t g = 0; g < longest; g += kItemsPerGroup)
+            for (size_t g = 0; g < longest; g += wpb)
                 for (int c = 0; c < kXcd; ++c)
-                    p->items.insert(p->items.end(), queue[c].begin() + g, queue[c].begin() + g + kItemsPerGroup);
+                    p->items.insert(p->items.end(), queue[c].begin() + g, queue[c].begin() + g + wpb);
         }
         for (int32_t len = short_max; len >= 0; --len)         // longest first, isolated rows last
             p->short_rows.insert(p->short_rows.end(), by_len[len].begin(), by_len[len].end());
@@ -337,7 +339,7 @@ mgg_status_t mgg_partition_info(const mgg_partition_t *p, mgg_partition_info_t *
     o->num_halo = static_cast<int64_t>(p->halo_gid.size());
     o->num_parts = p->num_parts; o->part_id = p->part_id;
     o->ps = p->ps; o->dist = p->dist; o->short_max = p->short_max; o->on_device = p->device >= 0;
-    o->xcd_min_deg = p->xcd_min_deg;
+    o->xcd_min_deg = p->xcd_min_deg; o->wpb = p->wpb;
     o->n_groups_local = p->n_groups_local; o->n_groups_remote = p->n_groups_remote;
     o->n_short_rows = static_cast<int64_t>(p->short_rows.size());
     o->n_items = static_cast<int64_t>(p->items.size());

@@ -126,7 +126,8 @@ def test_aggregate_bf16_dims(dim):
 @pytest.mark.parametrize("build", [dict(ps=1, dist=1), dict(ps=2, dist=3), dict(ps=7, dist=2), dict(ps=32, dist=1),
                                    dict(ps=64, dist=4), dict(ps=32, dist=1024), dict(short_max=-1),
                                    dict(short_max=4096), dict(ps=5, dist=5, short_max=3),
-                                   dict(xcd_min_deg=1, short_max=-1), dict(xcd_min_deg=40), dict(xcd_min_deg=500, dist=2)])
+                                   dict(xcd_min_deg=1, short_max=-1), dict(xcd_min_deg=40), dict(xcd_min_deg=500, dist=2),
+                                   dict(wpb=1), dict(wpb=2, xcd_min_deg=40), dict(wpb=8), dict(wpb=16, ps=16, dist=2)])
 def test_every_schedule_gives_the_same_answer(build):
     """Neighbour-partition size, pairs per work item and the short-row bin change only the
     schedule (section 4.1 Step-3, section 5.1), never the value."""

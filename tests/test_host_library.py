@@ -98,9 +98,9 @@ def _check_schedule(got, info):
         big = np.int64(1) << 32
         assert np.array_equal(np.sort(row_of * big + canon), np.sort(row_of * big + sched))
     if info.xcd_min_deg > 0:
-        assert got["item_row"].size % 32 == 0                           # 8 XCDs x 4 items per workgroup
+        assert got["item_row"].size % (8 * info.wpb) == 0                # 8 XCDs x wpb items per workgroup
         regrouped = deg[rows] >= info.xcd_min_deg
-        xcd = (pos // 4) % 8
+        xcd = (pos // info.wpb) % 8
         for i in np.nonzero(regrouped)[0][:4000]:
             cols = np.concatenate([got["sched_local_col"][lbeg[i]:lend[i]], got["sched_remote_col"][rbeg[i]:rend[i]]])
             assert cols.size and np.all(_source_class(cols) == xcd[i])
@@ -132,13 +132,14 @@ def test_partition_matches_hand_written_fixture():
 @pytest.mark.parametrize("parts,ps,dist,short_max", [(1, 0, 0, 0), (4, 32, 16, 16), (4, 2, 1, -1), (3, 7, 3, 5),
                                                      (8, 64, 1, 40), (2, 1, 1, 1)])
 def test_partition_bit_exact_against_oracle(parts, ps, dist, short_max, xcd_min_deg):
+    wpb = {-1: 0, 1: 1, 24: 16, 300: 3}[xcd_min_deg]
     rng = np.random.default_rng(parts * 100 + ps)
     row_ptr, col = inputs.rmat_graph(12, 50000, 0.57, 0.19, 0.19, 0.05, rng)
     n = row_ptr.size - 1
     bounds = inputs.equal_node_bounds(n, parts)
     for p in range(parts):
         _compare_with_oracle(row_ptr, col, parts, p, bounds, ps=ps, dist=dist, short_max=short_max,
-                             xcd_min_deg=xcd_min_deg)
+                             xcd_min_deg=xcd_min_deg, wpb=wpb)
 
 
 def test_partition_with_self_loops_duplicates_and_empty_ranges():
@@ -196,6 +197,7 @@ def test_bad_arguments_are_error_codes_not_crashes():
     assert _status(binding.mgg_build_partition, rp, col, 2, 0, [0, 1, 3], **ho) == binding.ERR_INVALID_ARG
     assert _status(binding.mgg_build_partition, rp, col, ps=65, **ho) == binding.ERR_INVALID_ARG
     assert _status(binding.mgg_build_partition, rp, col, dist=-3, **ho) == binding.ERR_INVALID_ARG
+    assert _status(binding.mgg_build_partition, rp, col, wpb=17, **ho) == binding.ERR_INVALID_ARG
     assert _status(binding.mgg_set_option, "no_such_option", 1) == binding.ERR_INVALID_ARG
     assert _status(binding.mgg_set_option, "lds_halo", 7) == binding.ERR_INVALID_ARG
     lib = binding.lib()
