@@ -141,6 +141,58 @@ def run_ablations(cfg: int, iters: int = 20):
     return rows
 
 
+def run_tuner(cfg: int, exhaustive: bool, iters: int = 10):
+    """The greedy search of section 6 (ps, dist, wpb) on layer 0's aggregation, driven with
+    measured latencies; with `exhaustive` the whole 6 x 5 x 5 grid is measured as well."""
+    import itertools
+    import torch
+    from paper_2209_06800_amd import binding, inputs
+    dev = "cuda:0"
+    w = inputs.config(cfg)
+    layer = w.layers[0]
+    esz = 2 if w.dtype == "bf16" else 4
+    pad = 128 if (w.dim * esz) % 16 else 0
+    part = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
+    info = part.info
+    hg = part.export()["halo_gid"]
+    xl = to_dev(w.x[w.lb:w.ub], dev, pad)
+    xh = to_dev(w.x[hg], dev, pad) if hg.size else None
+    out = torch.empty((int(info.n_own), w.dim), dtype=torch.float32, device=dev)
+    default_ms = binding.mgg_time_aggregate(part, layer.mode, xl, xh, out, eps=layer.eps, iters=iters)
+    default = (int(info.ps), int(info.dist), int(info.wpb))
+    part.destroy()
+    tuner = binding.Tuner(32, 16, 16)
+    t0 = time.time()
+    best, best_ms = binding.mgg_tune_aggregate(w.row_ptr, w.col, w.parts, w.part_id, w.bounds, layer.mode, xl, xh, out,
+                                               tuner, eps=layer.eps, iters=iters)
+    table = tuner.table()
+    res = {"workload": w.name, "default_knobs": default, "default_ms": round(default_ms, 4),
+           "search": {"trials": len(table), "best_knobs": best, "best_ms": round(best_ms, 4),
+                      "first_trial_ms": round(table[0][1], 4), "seconds": round(time.time() - t0, 1),
+                      "table": [[list(k), round(ms, 4)] for k, ms in table]}}
+    for k, ms in table:
+        log(f"[tune] trial ps={k[0]:2d} dist={k[1]:2d} wpb={k[2]:2d}: {ms:.4f} ms")
+    log(f"[tune] best {best}: {best_ms:.4f} ms after {len(table)} trials (default {default}: {default_ms:.4f} ms)")
+    if exhaustive:
+        grid = {}
+        for ps, dist, wpb in itertools.product([1, 2, 4, 8, 16, 32], [1, 2, 4, 8, 16], [1, 2, 4, 8, 16]):
+            try:
+                p2 = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds, ps=ps, dist=dist, wpb=wpb)
+                grid[(ps, dist, wpb)] = binding.mgg_time_aggregate(p2, layer.mode, xl, xh, out, eps=layer.eps, iters=iters)
+                p2.destroy()
+            except binding.MggError as e:
+                if e.status != binding.ERR_ALLOC:
+                    raise
+                grid[(ps, dist, wpb)] = float("inf")
+            log(f"[tune] grid ps={ps:2d} dist={dist:2d} wpb={wpb:2d}: {grid[(ps, dist, wpb)]:.4f} ms")
+        gbest = min(grid, key=grid.get)
+        res["exhaustive"] = {"configs": len(grid), "best_knobs": gbest, "best_ms": round(grid[gbest], 4),
+                             "search_best_over_grid_best": round(best_ms / grid[gbest], 4),
+                             "table": [[list(k), round(v, 4)] for k, v in grid.items()]}
+        log(f"[tune] grid best {gbest}: {grid[gbest]:.4f} ms; greedy / grid = {best_ms / grid[gbest]:.3f}")
+    return res
+
+
 def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 20.0, calibrate_copy: bool = False):
     import torch
     from paper_2209_06800_amd import binding, inputs
@@ -296,6 +348,10 @@ def main():
     ap.add_argument("--ablations", action="store_true",
                     help="time the aggregation of layer 0 with neighbour partitioning, interleaving, the XCD-aware "
                          "schedule, the short-row bin, LDS staging and column slabs switched one at a time, and exit")
+    ap.add_argument("--tune", action="store_true",
+                    help="run the greedy search over ps / dist / wpb (section 6) on layer 0's aggregation and exit")
+    ap.add_argument("--tune-exhaustive", action="store_true",
+                    help="like --tune, and measure the whole 150-point grid beside it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a 1 GiB device copy three times (reference for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -303,6 +359,9 @@ def main():
         print("bench.py measures one GPU's share on one MI355X; multi-GPU runs are not part of this build "
               "(no collectives, no second GPU). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    if args.tune or args.tune_exhaustive:
+        print(json.dumps(run_tuner(args.config, args.tune_exhaustive)), flush=True)
+        return
     if args.ablations:
         print(json.dumps({"workload_config": args.config, "ablations": run_ablations(args.config)}), flush=True)
         return

@@ -197,6 +197,52 @@ mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t 
 mgg_status_t mgg_split_edge_balanced(int64_t num_nodes, const int64_t *row_ptr, int32_t num_parts,
                                      int64_t *bounds_out);
 
+/* ---------------------------------------------------------------------------------------
+ * Analytical model and run-time parameter search -- section 6 ("Performance-Resource Analytical
+ * Modeling", "Heuristic-based Cross Iteration Optimization").  Host only.
+ *
+ * mgg_model_evaluate: equations (1)-(3).  wpw = 2 ps D dist (workload per wavefront);
+ * smem_bytes = ps wpb 4 + 2 wpb D 4 (the block-level layout of section 5.2: ids, partial
+ * results, fetched rows); num_waves = ceil(max(local, remote partitions) / dist);
+ * num_blocks = ceil(num_waves / wpb); blocks_per_unit = num_blocks / num_units (256 CUs on an
+ * MI355X); feasible = smem_bytes <= smem_limit_bytes (160 KB of LDS per CU).
+ *
+ * mgg_tuner_*: the greedy search.  All knobs start at 1; ps is doubled while the latency falls,
+ * then dist, then wpb; then ps is lowered step by step ("retreat") with the wpb search started
+ * again from 1, until a trial is slower than the third-lowest latency seen; every trial is kept
+ * in a lookup table and the lowest latency wins.  Usage: call mgg_tuner_next (it proposes a
+ * configuration, or sets *done), measure it, call mgg_tuner_report with the latency (any unit),
+ * repeat.  mgg_tuner_table copies up to `capacity` trials in the order they were made.
+ *
+ * mgg_tune_aggregate drives a tuner on the GPU: for every proposal it builds the partition with
+ * base_opts (NULL = defaults) plus the proposed ps / dist / wpb, times `iters` aggregations on
+ * `stream` with HIP events (synchronises), and reports the mean milliseconds.  Pointers as in
+ * mgg_build_partition and mgg_aggregate; `out` is overwritten by every trial.
+ * ------------------------------------------------------------------------------------- */
+typedef struct { int32_t ps, dist, wpb; } mgg_knobs_t;
+typedef struct {
+    int64_t wpw, smem_bytes, num_waves, num_blocks;
+    double  blocks_per_unit;
+    int32_t feasible;
+} mgg_model_t;
+typedef struct mgg_tuner mgg_tuner_t;
+
+mgg_status_t mgg_model_evaluate(int64_t n_local_partitions, int64_t n_remote_partitions, mgg_knobs_t knobs,
+                                int32_t dim, int32_t num_units, int64_t smem_limit_bytes, mgg_model_t *out);
+mgg_status_t mgg_tuner_create(int32_t ps_max, int32_t dist_max, int32_t wpb_max, mgg_tuner_t **out);
+mgg_status_t mgg_tuner_next(mgg_tuner_t *t, mgg_knobs_t *next, int32_t *done);
+mgg_status_t mgg_tuner_report(mgg_tuner_t *t, double latency);
+mgg_status_t mgg_tuner_result(const mgg_tuner_t *t, mgg_knobs_t *best, double *best_latency, int32_t *n_trials);
+mgg_status_t mgg_tuner_table(const mgg_tuner_t *t, int32_t capacity, mgg_knobs_t *knobs, double *latency,
+                             int32_t *n_trials);
+void         mgg_tuner_destroy(mgg_tuner_t *t);   /* NULL is allowed */
+mgg_status_t mgg_tune_aggregate(int64_t num_nodes, const int64_t *row_ptr, const int32_t *col_idx,
+                                int32_t num_parts, int32_t part_id, const int64_t *bounds,
+                                const mgg_build_opts_t *base_opts, mgg_agg_t mode, float eps,
+                                mgg_dtype_t x_dtype, const void *x_local, const void *x_halo, int32_t dim,
+                                int64_t ld_x, float *out, int64_t ld_out, void *stream, int32_t iters,
+                                mgg_tuner_t *tuner, mgg_knobs_t *best, double *best_ms);
+
 /* Run-time switches for experiments (ablations of section 7.2's kind).  Known keys:
  *   "xcd_remap"   0/1  contiguous chunks of work items per XCD            (default 1)
  *   "lds_halo"    0/1  stage halo rows through LDS ahead of accumulation  (default 0)

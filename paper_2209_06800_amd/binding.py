@@ -27,6 +27,8 @@ EXPORTED_SYMBOLS = [
     "mgg_build_partition", "mgg_partition_info", "mgg_partition_export", "mgg_partition_destroy",
     "mgg_aggregate", "mgg_update", "mgg_layer_workspace_bytes", "mgg_layer_forward",
     "mgg_split_edge_balanced", "mgg_set_option", "mgg_get_option", "mgg_time_aggregate",
+    "mgg_model_evaluate", "mgg_tuner_create", "mgg_tuner_next", "mgg_tuner_report", "mgg_tuner_result",
+    "mgg_tuner_table", "mgg_tuner_destroy", "mgg_tune_aggregate",
     "mgg_last_error", "mgg_version",
 ]
 
@@ -62,6 +64,15 @@ _ARRAY_FIELDS = ["local_row_ptr", "local_col", "remote_row_ptr", "remote_col", "
 
 class PartitionArrays(C.Structure):
     _fields_ = [(name, C.c_void_p) for name in _ARRAY_FIELDS]
+
+
+class Knobs(C.Structure):
+    _fields_ = [("ps", C.c_int32), ("dist", C.c_int32), ("wpb", C.c_int32)]
+
+
+class Model(C.Structure):
+    _fields_ = [("wpw", C.c_int64), ("smem_bytes", C.c_int64), ("num_waves", C.c_int64), ("num_blocks", C.c_int64),
+                ("blocks_per_unit", C.c_double), ("feasible", C.c_int32)]
 
 
 class LayerDesc(C.Structure):
@@ -106,6 +117,20 @@ def lib():
         L.mgg_time_aggregate.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p,
                                          C.c_int32, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                                          C.POINTER(C.c_float)]
+        L.mgg_model_evaluate.argtypes = [C.c_int64, C.c_int64, Knobs, C.c_int32, C.c_int32, C.c_int64,
+                                         C.POINTER(Model)]
+        L.mgg_tuner_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+        L.mgg_tuner_next.argtypes = [C.c_void_p, C.POINTER(Knobs), C.POINTER(C.c_int32)]
+        L.mgg_tuner_report.argtypes = [C.c_void_p, C.c_double]
+        L.mgg_tuner_result.argtypes = [C.c_void_p, C.POINTER(Knobs), C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+        L.mgg_tuner_table.argtypes = [C.c_void_p, C.c_int32, C.POINTER(Knobs), C.POINTER(C.c_double),
+                                      C.POINTER(C.c_int32)]
+        L.mgg_tuner_destroy.restype = None
+        L.mgg_tuner_destroy.argtypes = [C.c_void_p]
+        L.mgg_tune_aggregate.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                         C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_int32,
+                                         C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p,
+                                         C.POINTER(Knobs), C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -312,3 +337,77 @@ def mgg_layer_forward(part: Partition, mode: str, x_local, x_halo, weights, acts
                                    _dev_ptr(x_halo), _ld(x_local), _dev_ptr(workspace), workspace.numel(),
                                    _torch_dtype_code(out), _dev_ptr(out), _ld(out), _stream(stream)))
     return out
+
+
+# ------------------------------------------------------------------------------- model and tuner
+def mgg_model_evaluate(n_local_partitions: int, n_remote_partitions: int, ps: int, dist: int, wpb: int, dim: int,
+                       num_units: int = 256, smem_limit_bytes: int = 160 * 1024) -> dict:
+    m = Model()
+    _check(lib().mgg_model_evaluate(n_local_partitions, n_remote_partitions, Knobs(ps, dist, wpb), dim, num_units,
+                                    smem_limit_bytes, C.byref(m)))
+    return {"wpw": m.wpw, "smem": m.smem_bytes, "num_warps": m.num_waves, "num_blocks": m.num_blocks,
+            "blocks_per_unit": m.blocks_per_unit, "feasible": bool(m.feasible)}
+
+
+class Tuner:
+    """Owner of an ``mgg_tuner_t*`` (propose / report search over ps, dist, wpb)."""
+
+    def __init__(self, ps_max: int = 32, dist_max: int = 16, wpb_max: int = 16):
+        h = C.c_void_p()
+        _check(lib().mgg_tuner_create(ps_max, dist_max, wpb_max, C.byref(h)))
+        self._h = h
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("tuner already destroyed")
+        return self._h
+
+    def next(self):
+        """The next configuration (ps, dist, wpb) to measure, or None when the search is over."""
+        k, done = Knobs(), C.c_int32()
+        _check(lib().mgg_tuner_next(self.handle, C.byref(k), C.byref(done)))
+        return None if done.value else (k.ps, k.dist, k.wpb)
+
+    def report(self, latency: float):
+        _check(lib().mgg_tuner_report(self.handle, float(latency)))
+
+    def result(self):
+        k, lat, n = Knobs(), C.c_double(), C.c_int32()
+        _check(lib().mgg_tuner_result(self.handle, C.byref(k), C.byref(lat), C.byref(n)))
+        return (k.ps, k.dist, k.wpb), lat.value, n.value
+
+    def table(self):
+        n = C.c_int32()
+        _check(lib().mgg_tuner_table(self.handle, 0, None, None, C.byref(n)))
+        ks, lats = (Knobs * max(n.value, 1))(), (C.c_double * max(n.value, 1))()
+        _check(lib().mgg_tuner_table(self.handle, n.value, ks, lats, C.byref(n)))
+        return [((ks[i].ps, ks[i].dist, ks[i].wpb), lats[i]) for i in range(n.value)]
+
+    def destroy(self):
+        if self._h is not None:
+            lib().mgg_tuner_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def mgg_tune_aggregate(row_ptr: np.ndarray, col_idx: np.ndarray, num_parts: int, part_id: int, bounds, mode: str,
+                       x_local, x_halo, out, tuner: Tuner, *, eps: float = 0.0, iters: int = 10,
+                       base_opts: Optional[BuildOpts] = None, stream=None):
+    """Runs the search on the GPU; returns ((ps, dist, wpb), best milliseconds)."""
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    b = None if bounds is None else np.ascontiguousarray(bounds, dtype=np.int64)
+    k, ms = Knobs(), C.c_double()
+    dim = int(x_local.shape[1])
+    _check(lib().mgg_tune_aggregate(row_ptr.size - 1, _np_ptr(row_ptr), _np_ptr(col_idx), num_parts, part_id,
+                                    _np_ptr(b), None if base_opts is None else C.byref(base_opts), _MODE[mode], eps,
+                                    _torch_dtype_code(x_local), _dev_ptr(x_local), _dev_ptr(x_halo), dim,
+                                    _ld(x_local), _dev_ptr(out), _ld(out), _stream(stream), iters, tuner.handle,
+                                    C.byref(k), C.byref(ms)))
+    return (k.ps, k.dist, k.wpb), ms.value

@@ -372,3 +372,29 @@ def test_aggregate_cfg2_full_size_sampled_rows():
     heavy = np.argsort(deg)[-8:]
     sample = np.unique(np.concatenate([heavy, rng.integers(0, w.ub - w.lb, 400), np.nonzero(deg == 0)[0][:8]]))
     check_aggregate(w.row_ptr, w.col, w.parts, w.part_id, w.bounds, w.x, "gcn", rows=sample, what="cfg2 full")
+
+
+# ----------------------------------------------------------------------------- run-time search
+def test_tune_aggregate_runs_the_search_on_the_gpu():
+    """mgg_tune_aggregate drives the propose / report search with measured latencies: every
+    trial is a legal configuration measured once, the winner is the table's minimum, and a
+    partition built with the winning knobs still matches the oracle."""
+    w = inputs.config(2, shrink=4)
+    ref_part = oracle.build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
+    lb, ub, hg = ref_part["lb"], ref_part["ub"], ref_part["halo_gid"]
+    xl, xh = to_dev(w.x[lb:ub]), to_dev(w.x[hg])
+    out = torch.empty((ub - lb, w.dim), dtype=torch.float32, device=DEV)
+    tuner = binding.Tuner(32, 16, 16)
+    best, best_ms = binding.mgg_tune_aggregate(w.row_ptr, w.col, w.parts, w.part_id, w.bounds, "gcn", xl, xh, out,
+                                               tuner, iters=3)
+    table = tuner.table()
+    assert tuner.next() is None                                     # the search has ended
+    assert table[0][0] == (1, 1, 1) and table[1][0] == (2, 1, 1)    # all knobs start at 1, ps moves first
+    assert len({k for k, _ in table}) == len(table) <= 6 + 5 + 5 + 30
+    assert all(ps in (1, 2, 4, 8, 16, 32) and d in (1, 2, 4, 8, 16) and b in (1, 2, 4, 8, 16) for (ps, d, b), _ in table)
+    assert all(ms > 0 for _, ms in table)
+    assert (best, best_ms) == min(table, key=lambda kv: kv[1])
+    assert best_ms < table[0][1]                                    # better than the starting point
+    tuner.destroy()
+    check_aggregate(w.row_ptr, w.col, w.parts, w.part_id, w.bounds, w.x, "gcn",
+                    build=dict(ps=best[0], dist=best[1], wpb=best[2]), what=f"tuned {best}")
