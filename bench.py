@@ -193,6 +193,51 @@ def run_tuner(cfg: int, exhaustive: bool, iters: int = 10):
     return res
 
 
+def calibrate_gather(dims=(64, 100, 256), n_halo: int = 1 << 22, per_row: int = 32, launches: int = 2):
+    """Launches the aggregation kernel on two graphs whose cache behaviour is known by construction.
+
+    cold: part 0 of 2 owns n_halo / per_row rows, each with per_row neighbours that together form
+    one random permutation of the n_halo rows of part 1.  Every halo row (>= 1 GiB in total, far
+    beyond L2 and the Infinity Cache) is gathered exactly once per launch: all gathers miss, the
+    L2-miss bytes are known, and a counter run (rocprofv3 --pmc FETCH_SIZE) can be scaled for
+    gather traffic, not only for streaming.
+
+    hot: the same number of gathers, but drawn from 4096 halo rows only (at most 4 MB, resident in
+    every XCD's L2): all gathers hit.  The two rates bracket what any schedule can reach."""
+    import torch
+    from paper_2209_06800_amd import binding
+    dev = "cuda:0"
+    n_dst = n_halo // per_row
+    rng = np.random.default_rng(5)
+    out_lines = []
+    for kind in ("cold", "hot"):
+        n_src = n_halo if kind == "cold" else 4096
+        row_ptr = np.zeros(n_dst + n_src + 1, dtype=np.int64)
+        row_ptr[1:n_dst + 1] = per_row * np.arange(1, n_dst + 1)
+        row_ptr[n_dst + 1:] = row_ptr[n_dst]
+        if kind == "cold":
+            src = rng.permutation(n_halo).reshape(n_dst, per_row)
+        else:
+            src = rng.integers(0, n_src, size=(n_dst, per_row))
+        col = (n_dst + np.sort(src, axis=1).ravel()).astype(np.int32)
+        part = binding.mgg_build_partition(row_ptr, col, 2, 0, [0, n_dst, n_dst + n_src], xcd_min_deg=-1)
+        for dim in dims:
+            xl = torch.empty((n_dst, dim), dtype=torch.float32, device=dev).normal_()
+            xh = torch.empty((n_src, dim), dtype=torch.float32, device=dev).normal_()
+            out = torch.empty((n_dst, dim), dtype=torch.float32, device=dev)
+            ms = binding.mgg_time_aggregate(part, "gin", xl, xh, out, iters=launches)
+            gathered = n_halo * dim * 4
+            expect = (n_halo if kind == "cold" else n_src) * dim * 4 + n_halo * 4 + n_dst * (dim * 4 + 12)
+            out_lines.append({"kind": kind, "dim": dim, "row_bytes": dim * 4, "gathers": n_halo, "table_rows": n_src,
+                              "expected_fetch_bytes": expect, "ms": round(ms, 4),
+                              "gathered_gbs": round(gathered / ms / 1e6, 1)})
+            log(f"[calibrate-gather] {kind} dim {dim}: {n_halo} gathers of {dim * 4} B from {n_src} table rows; "
+                f"expected L2-miss reads {expect} B per launch; {ms:.4f} ms = {gathered / ms / 1e6:.0f} GB/s gathered")
+            del xl, xh, out
+        part.destroy()
+    return out_lines
+
+
 def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 20.0, calibrate_copy: bool = False):
     import torch
     from paper_2209_06800_amd import binding, inputs
@@ -352,6 +397,9 @@ def main():
                     help="run the greedy search over ps / dist / wpb (section 6) on layer 0's aggregation and exit")
     ap.add_argument("--tune-exhaustive", action="store_true",
                     help="like --tune, and measure the whole 150-point grid beside it")
+    ap.add_argument("--calibrate-gather", action="store_true",
+                    help="launch the aggregation kernel on a graph that gathers each of 4 Mi table rows exactly once "
+                         "(known L2-miss bytes; reference for rocprofv3 --pmc runs) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a 1 GiB device copy three times (reference for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -359,6 +407,9 @@ def main():
         print("bench.py measures one GPU's share on one MI355X; multi-GPU runs are not part of this build "
               "(no collectives, no second GPU). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    if args.calibrate_gather:
+        print(json.dumps({"calibrate_gather": calibrate_gather()}), flush=True)
+        return
     if args.tune or args.tune_exhaustive:
         print(json.dumps(run_tuner(args.config, args.tune_exhaustive)), flush=True)
         return

@@ -41,7 +41,8 @@ class MggError(RuntimeError):
 
 class BuildOpts(C.Structure):
     _fields_ = [("ps", C.c_int32), ("dist", C.c_int32), ("short_max", C.c_int32), ("host_only", C.c_int32),
-                ("wpb", C.c_int32), ("xcd_min_deg", C.c_int32)]
+                ("wpb", C.c_int32), ("xcd_min_deg", C.c_int32), ("hot_row_bytes", C.c_int32), ("hot_rows", C.c_int32),
+                ("hot_phases", C.c_int32), ("min_piece", C.c_int32), ("hot_min_count", C.c_int32)]
 
 
 class PartitionInfo(C.Structure):
@@ -50,6 +51,7 @@ class PartitionInfo(C.Structure):
                 ("num_parts", C.c_int32), ("part_id", C.c_int32),
                 ("ps", C.c_int32), ("dist", C.c_int32), ("short_max", C.c_int32), ("on_device", C.c_int32),
                 ("xcd_min_deg", C.c_int32), ("wpb", C.c_int32),
+                ("hot_rows", C.c_int32), ("n_phases", C.c_int32), ("min_piece", C.c_int32), ("hot_min_count", C.c_int32),
                 ("n_groups_local", C.c_int64), ("n_groups_remote", C.c_int64),
                 ("n_short_rows", C.c_int64), ("n_items", C.c_int64),
                 ("n_split_rows", C.c_int64), ("n_split_items", C.c_int64)]
@@ -59,7 +61,8 @@ _ARRAY_FIELDS = ["local_row_ptr", "local_col", "remote_row_ptr", "remote_col", "
                  "deg_own", "deg_halo", "grp_local_row", "grp_local_start", "grp_local_end",
                  "grp_remote_row", "grp_remote_start", "grp_remote_end", "short_rows",
                  "sched_local_col", "sched_remote_col",
-                 "item_row", "item_lbeg", "item_lend", "item_rbeg", "item_rend", "item_slot"]
+                 "item_row", "item_lbeg", "item_lend", "item_rbeg", "item_rend", "item_slot",
+                 "src_class_local", "src_class_halo"]
 
 
 class PartitionArrays(C.Structure):
@@ -217,6 +220,7 @@ class Partition:
             "sched_local_col": i.nnz_local, "sched_remote_col": i.nnz_remote,
             "item_row": i.n_items, "item_lbeg": i.n_items, "item_lend": i.n_items, "item_rbeg": i.n_items,
             "item_rend": i.n_items, "item_slot": i.n_items,
+            "src_class_local": i.n_own, "src_class_halo": i.num_halo,
         }
         out = {k: np.zeros(max(int(n), 0), dtype=np.int64 if k == "halo_peer_ptr" else np.int32)
                for k, n in sizes.items()}
@@ -228,14 +232,16 @@ class Partition:
 def mgg_build_partition(row_ptr: np.ndarray, col_idx: np.ndarray, num_parts: int = 1, part_id: int = 0,
                         bounds: Optional[Sequence[int]] = None, *, ps: int = 0, dist: int = 0,
                         short_max: int = 0, host_only: bool = False, xcd_min_deg: int = 0, wpb: int = 0,
-                        num_nodes: Optional[int] = None) -> Partition:
+                        hot_row_bytes: int = 0, hot_rows: int = 0, hot_phases: int = 0, min_piece: int = 0,
+                        hot_min_count: int = 0, num_nodes: Optional[int] = None) -> Partition:
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
     n = row_ptr.size - 1 if num_nodes is None else num_nodes
     b = None if bounds is None else np.ascontiguousarray(bounds, dtype=np.int64)
     if b is not None and b.size != num_parts + 1:
         raise MggError(ERR_INVALID_ARG, "bounds must have num_parts + 1 entries")
-    opts = BuildOpts(ps, dist, short_max, int(host_only), wpb, xcd_min_deg)
+    opts = BuildOpts(ps, dist, short_max, int(host_only), wpb, xcd_min_deg, hot_row_bytes, hot_rows, hot_phases,
+                     min_piece, hot_min_count)
     h = C.c_void_p()
     _check(lib().mgg_build_partition(n, _np_ptr(row_ptr), _np_ptr(col_idx) if col_idx.size else None,
                                      num_parts, part_id, _np_ptr(b), C.byref(opts), C.byref(h)))

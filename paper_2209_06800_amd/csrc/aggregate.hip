@@ -30,7 +30,8 @@ constexpr int kMaxWpb = 16;                         // wavefronts per workgroup 
 
 struct AggArgs {
     const int32_t *local_row_ptr, *local_col, *remote_row_ptr, *remote_col;
-    const float *dinv_own, *dinv_halo;
+    const float *dinv_own;               // 1/sqrt(deg+1) of the owned rows (the row factor of GCN)
+    const float *w_local, *w_remote;     // GCN: factor of the neighbour, one per entry of the column arrays
     const int32_t *short_rows;
     const WorkItem *items;
     const void *x_local, *x_halo;
@@ -203,21 +204,22 @@ __device__ __forceinline__ void accumulate_partition(Acc<K> &acc, const typename
     }
 }
 
-// Load the ids (and GCN factors) of the partition starting at `pos`, one per lane.
-__device__ __forceinline__ void load_partition_ids(const int32_t *col, const float *dinv, int pos, int len, int lane,
+// Load the ids (and GCN factors) of the partition starting at `pos`, one per lane.  The factors
+// are stored per edge, in the order of the column array, so both loads are coalesced.
+__device__ __forceinline__ void load_partition_ids(const int32_t *col, const float *wts, int pos, int len, int lane,
                                                    bool gcn, int &idx, float &w)
 {
     idx = 0; w = 0.f;
     if (lane < len) {
         idx = col[pos + lane];
-        w = gcn ? dinv[idx] : 1.f;
+        w = gcn ? wts[pos + lane] : 1.f;
     }
 }
 
 // Sub-wave walk over one short neighbour list (all lanes of the sub-wave read the same id).
 template <class K>
 __device__ __forceinline__ void accumulate_list(Acc<K> &acc, const typename K::elem *table, int64_t ld,
-                                                const int32_t *col, const float *dinv, int beg, int end,
+                                                const int32_t *col, const float *wts, int beg, int end,
                                                 bool gcn, int lis, int nvec)
 {
     for (int j0 = beg; j0 < end; j0 += K::U) {
@@ -227,7 +229,7 @@ __device__ __forceinline__ void accumulate_list(Acc<K> &acc, const typename K::e
         for (int u = 0; u < K::U; ++u) {
             const bool ok = j0 + u < end;
             const int idx = ok ? col[j0 + u] : 0;
-            w[u] = ok ? (gcn ? dinv[idx] : 1.f) : 0.f;
+            w[u] = ok ? (gcn ? wts[j0 + u] : 1.f) : 0.f;
             const typename K::elem *rowp = table + static_cast<int64_t>(idx) * ld;
 #pragma unroll
             for (int c = 0; c < K::CH; ++c) {
@@ -334,13 +336,13 @@ __global__ __launch_bounds__(kWave * kMaxWpb) void aggregate_kernel(const AggArg
         const int g_n = g_l > g_r ? g_l : g_r;
         int idx_l, idx_r, nidx_l = 0, nidx_r = 0;
         float w_l, w_r, nw_l = 0.f, nw_r = 0.f;
-        load_partition_ids(a.local_col, a.dinv_own, it.lbeg, min(ps, n_l), lane, gcn, idx_l, w_l);
-        load_partition_ids(a.remote_col, a.dinv_halo, it.rbeg, min(ps, n_r), lane, gcn, idx_r, w_r);
+        load_partition_ids(a.local_col, a.w_local, it.lbeg, min(ps, n_l), lane, gcn, idx_l, w_l);
+        load_partition_ids(a.remote_col, a.w_remote, it.rbeg, min(ps, n_r), lane, gcn, idx_r, w_r);
         for (int g = 0; g < g_n; ++g) {
             // ids of the next pair are requested before this pair's rows are gathered
             const int off = (g + 1) * ps;
-            load_partition_ids(a.local_col, a.dinv_own, it.lbeg + off, min(ps, n_l - off), lane, gcn, nidx_l, nw_l);
-            load_partition_ids(a.remote_col, a.dinv_halo, it.rbeg + off, min(ps, n_r - off), lane, gcn, nidx_r, nw_r);
+            load_partition_ids(a.local_col, a.w_local, it.lbeg + off, min(ps, n_l - off), lane, gcn, nidx_l, nw_l);
+            load_partition_ids(a.remote_col, a.w_remote, it.rbeg + off, min(ps, n_r - off), lane, gcn, nidx_r, nw_r);
             const int len_l = min(ps, n_l - g * ps), len_r = min(ps, n_r - g * ps);
             if constexpr (LDSH) {
                 uint4 (*stage)[kWave] = stage_all[wave];
@@ -371,10 +373,10 @@ __global__ __launch_bounds__(kWave * kMaxWpb) void aggregate_kernel(const AggArg
         if (s_id >= a.n_short) return;
         const int32_t row = a.short_rows[s_id];
         if (a.phase != 2)
-            accumulate_list<K>(acc, xl, a.ld_x, a.local_col, a.dinv_own, a.local_row_ptr[row], a.local_row_ptr[row + 1],
+            accumulate_list<K>(acc, xl, a.ld_x, a.local_col, a.w_local, a.local_row_ptr[row], a.local_row_ptr[row + 1],
                                gcn, lis, vend);
         if (a.phase != 1)
-            accumulate_list<K>(acc, xh, a.ld_x, a.remote_col, a.dinv_halo, a.remote_row_ptr[row], a.remote_row_ptr[row + 1],
+            accumulate_list<K>(acc, xh, a.ld_x, a.remote_col, a.w_remote, a.remote_row_ptr[row], a.remote_row_ptr[row + 1],
                                gcn, lis, vend);
         write_final<K>(a, acc, row, lis, vend);
     }
@@ -516,7 +518,7 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
     AggArgs a{};
     a.local_row_ptr = p->d.local_row_ptr; a.local_col = p->d.local_col;
     a.remote_row_ptr = p->d.remote_row_ptr; a.remote_col = p->d.remote_col;
-    a.dinv_own = p->d.dinv_own; a.dinv_halo = p->d.dinv_halo;
+    a.dinv_own = p->d.dinv_own; a.w_local = p->d.w_local; a.w_remote = p->d.w_remote;
     a.short_rows = p->d.short_rows; a.items = p->d.items;
     a.x_local = x_local; a.x_halo = xh;
     a.out = out; a.scratch = p->d.scratch;

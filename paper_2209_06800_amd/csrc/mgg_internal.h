@@ -36,11 +36,18 @@ struct SplitRow {
 constexpr int kXcd = 8;             // accelerator complex dies of an MI355X, each with its own L2
 constexpr int kDefaultWpb = 4;      // work items (wavefronts) per workgroup of the aggregation kernel
 constexpr int kDefaultXcdMinDeg = 256;
+constexpr int kDefaultHotPhases = -1;       // 8 classes by hash; popularity-ranked phases are opt-in
+constexpr int kMaxHotPhases = 31;           // class index phase * 8 + XCD has to stay below kColdClass
+constexpr int kDefaultMinPiece = 16;        // a class with fewer neighbours in a row joins the row's cold piece
+constexpr int kDefaultHotMinCount = 8;      // table rows gathered fewer times than this are never hot
+constexpr int kColdClass = 255;
+constexpr int64_t kHotBytesPerXcd = 3 << 20;   // of the 4 MB L2 of one XCD, what the hot rows of a phase may fill
 
 struct DeviceArrays {
     int32_t *local_row_ptr = nullptr, *local_col = nullptr;
     int32_t *remote_row_ptr = nullptr, *remote_col = nullptr;
-    float *dinv_own = nullptr, *dinv_halo = nullptr;
+    float *dinv_own = nullptr;
+    float *w_local = nullptr, *w_remote = nullptr;   // 1/sqrt(deg+1) of the neighbour, per entry of the column arrays
     int32_t *short_rows = nullptr;
     WorkItem *items = nullptr;
     SplitRow *split_rows = nullptr;
@@ -54,6 +61,8 @@ struct mgg_partition {
     int64_t num_nodes = 0, lb = 0, ub = 0, n_own = 0;
     int32_t num_parts = 1, part_id = 0;
     int32_t ps = 32, dist = 16, short_max = 16, xcd_min_deg = -1, wpb = 4;
+    int32_t hot_rows = 0, hot_phases = 0, n_phases = 0, min_piece = 0, hot_min_count = 0;
+    std::vector<uint8_t> src_class;   // class of every table row (local rows, then halo slots); empty: no classes
     int device = -1;  // HIP device the arrays live on; -1 = host only
     std::vector<int32_t> local_row_ptr, local_col, remote_row_ptr, remote_col;
     std::vector<int32_t> sched_local_col, sched_remote_col;   // device order of the columns (empty: same as above)

@@ -45,8 +45,8 @@ static void free_device(mgg_partition *p)
 {
     if (p->device < 0) return;
     DeviceArrays &d = p->d;
-    void *ptrs[] = {d.local_row_ptr, d.local_col, d.remote_row_ptr, d.remote_col, d.dinv_own,
-                    d.dinv_halo,     d.short_rows, d.items,         d.split_rows, d.scratch};
+    void *ptrs[] = {d.local_row_ptr, d.local_col, d.remote_row_ptr, d.remote_col, d.dinv_own, d.w_local,
+                    d.w_remote,      d.short_rows, d.items,         d.split_rows, d.scratch};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
     d = DeviceArrays{};
@@ -63,7 +63,18 @@ static mgg_status_t upload_all(mgg_partition *p)
     if ((s = upload(p->remote_row_ptr, &p->d.remote_row_ptr)) != MGG_OK) return s;
     if ((s = upload(p->sched_remote_col.empty() ? p->remote_col : p->sched_remote_col, &p->d.remote_col)) != MGG_OK) return s;
     if ((s = upload(p->dinv_own, &p->d.dinv_own)) != MGG_OK) return s;
-    if ((s = upload(p->dinv_halo, &p->d.dinv_halo)) != MGG_OK) return s;
+    {
+        // the neighbour's factor, stored per edge in the order the kernel walks the columns: a
+        // coalesced stream instead of a 4-byte gather per neighbour
+        const std::vector<int32_t> &lc = p->sched_local_col.empty() ? p->local_col : p->sched_local_col;
+        const std::vector<int32_t> &rc = p->sched_remote_col.empty() ? p->remote_col : p->sched_remote_col;
+        std::vector<float> w(lc.size());
+        for (size_t i = 0; i < lc.size(); ++i) w[i] = p->dinv_own[lc[i]];
+        if ((s = upload(w, &p->d.w_local)) != MGG_OK) return s;
+        w.resize(rc.size());
+        for (size_t i = 0; i < rc.size(); ++i) w[i] = p->dinv_halo[rc[i]];
+        if ((s = upload(w, &p->d.w_remote)) != MGG_OK) return s;
+    }
     if ((s = upload(p->short_rows, &p->d.short_rows)) != MGG_OK) return s;
     if ((s = upload(p->items, &p->d.items)) != MGG_OK) return s;
     if ((s = upload(p->split_rows, &p->d.split_rows)) != MGG_OK) return s;
@@ -114,7 +125,14 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
     if (num_parts < 1 || part_id < 0 || part_id >= num_parts)
         return fail(MGG_ERR_INVALID_ARG, "part_id %d outside [0, %d)", part_id, num_parts);
     int32_t ps = 32, dist = 16, short_max = 16, host_only = 0, xcd_min_deg = kDefaultXcdMinDeg, wpb = kDefaultWpb;
+    int32_t hot_rows = 0, hot_phases = kDefaultHotPhases, min_piece = kDefaultMinPiece, hot_min_count = kDefaultHotMinCount;
+    int32_t hot_row_bytes = 256;
     if (opts) {
+        if (opts->hot_row_bytes) hot_row_bytes = opts->hot_row_bytes;
+        if (opts->hot_rows) hot_rows = opts->hot_rows;
+        if (opts->hot_phases) hot_phases = opts->hot_phases;
+        if (opts->min_piece) min_piece = opts->min_piece;
+        if (opts->hot_min_count) hot_min_count = opts->hot_min_count;
         if (opts->ps) ps = opts->ps;
         if (opts->dist) dist = opts->dist;
         if (opts->short_max) short_max = opts->short_max;
@@ -126,6 +144,16 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
     if (dist < 1 || dist > 1024) return fail(MGG_ERR_INVALID_ARG, "dist %d outside [1, 1024]", dist);
     if (short_max > 4096) return fail(MGG_ERR_INVALID_ARG, "short_max %d above 4096", short_max);
     if (wpb < 1 || wpb > 16) return fail(MGG_ERR_INVALID_ARG, "wpb %d outside [1, 16]", wpb);
+    if (hot_row_bytes < 1 || hot_row_bytes > (1 << 20)) return fail(MGG_ERR_INVALID_ARG, "hot_row_bytes %d outside [1, 2^20]", hot_row_bytes);
+    if (hot_rows == 0) {
+        // as many table rows as fit kHotBytesPerXcd of one XCD's L2, rows counted in whole 128-byte lines
+        const int64_t line_bytes = (static_cast<int64_t>(hot_row_bytes) + 127) / 128 * 128;
+        hot_rows = static_cast<int32_t>(std::max<int64_t>(1, kHotBytesPerXcd / line_bytes));
+    }
+    if (hot_rows < 1 || hot_rows > (1 << 24)) return fail(MGG_ERR_INVALID_ARG, "hot_rows %d outside [1, 2^24]", hot_rows);
+    if (hot_phases > kMaxHotPhases) return fail(MGG_ERR_INVALID_ARG, "hot_phases %d above %d", hot_phases, kMaxHotPhases);
+    if (min_piece < 1) return fail(MGG_ERR_INVALID_ARG, "min_piece %d below 1", min_piece);
+    if (hot_min_count < 1) return fail(MGG_ERR_INVALID_ARG, "hot_min_count %d below 1", hot_min_count);
 
     // ---- validate the graph ------------------------------------------------------------
     if (row_ptr[0] != 0) return fail(MGG_ERR_BAD_GRAPH, "row_ptr[0] != 0");
@@ -159,6 +187,7 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
         p->num_nodes = num_nodes; p->lb = lb; p->ub = ub; p->n_own = n_own;
         p->num_parts = num_parts; p->part_id = part_id;
         p->ps = ps; p->dist = dist; p->short_max = short_max; p->xcd_min_deg = xcd_min_deg; p->wpb = wpb;
+        p->hot_rows = hot_rows; p->hot_phases = hot_phases; p->min_piece = min_piece; p->hot_min_count = hot_min_count;
 
         // ---- pass 1: count local / remote per owned row, mark halo nodes -----------------
         std::vector<uint8_t> is_halo(static_cast<size_t>(num_nodes), 0);
@@ -219,32 +248,71 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
             p->dinv_halo[h] = static_cast<float>(1.0 / std::sqrt(static_cast<double>(p->deg_halo[h]) + 1.0));
         }
 
+        // ---- source classes -------------------------------------------------------------
+        // Every row of the two embedding tables gets a class.  Default (hot_phases < 0): a hash of
+        // its index, 8 classes, one per XCD, no cold class.  With hot_phases >= 1 the class is
+        // either (phase, XCD) -- "hot" -- or cold, and hot classes are filled in order of popularity (how many owned rows gather the
+        // table row): the 8*hot_rows most gathered rows form phase 0, dealt round-robin to the
+        // 8 XCDs, the next 8*hot_rows phase 1, and so on.  An XCD works through its phases in
+        // order, so at any time its L2 only has to hold hot_rows table rows, all of which are
+        // gathered many times.
+        const bool use_classes = xcd_min_deg > 0;
+        const int64_t n_tab = n_own + num_halo;                  // local rows first, then halo slots
+        int n_phase = 0;
+        if (use_classes) {
+            p->src_class.assign(static_cast<size_t>(n_tab), kColdClass);
+            if (hot_phases < 0) {
+                n_phase = 1;
+                for (int64_t i = 0; i < n_own; ++i) p->src_class[i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
+                for (int64_t i = 0; i < num_halo; ++i) p->src_class[n_own + i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
+            } else if (n_tab > 0) {
+                std::vector<int32_t> cnt(static_cast<size_t>(n_tab), 0);
+                for (int32_t u : p->local_col) ++cnt[u];
+                for (int32_t u : p->remote_col) ++cnt[n_own + u];
+                // counting sort of the table rows by gather count, most gathered first (ties: lower index first)
+                const int32_t max_cnt = *std::max_element(cnt.begin(), cnt.end());
+                std::vector<int64_t> start(static_cast<size_t>(max_cnt) + 2, 0);
+                for (int64_t i = 0; i < n_tab; ++i) ++start[max_cnt - cnt[i] + 1];
+                for (size_t c = 1; c < start.size(); ++c) start[c] += start[c - 1];
+                std::vector<int32_t> order(static_cast<size_t>(n_tab));
+                for (int64_t i = 0; i < n_tab; ++i) order[start[max_cnt - cnt[i]]++] = static_cast<int32_t>(i);
+                const int64_t per_phase = static_cast<int64_t>(kXcd) * hot_rows;
+                const int64_t limit = std::min<int64_t>(n_tab, per_phase * hot_phases);
+                int64_t r = 0;
+                for (; r < limit && cnt[order[r]] >= hot_min_count; ++r)
+                    p->src_class[order[r]] = static_cast<uint8_t>((r / per_phase) * kXcd + r % kXcd);
+                n_phase = static_cast<int>(ceil_div(r, per_phase));
+            }
+        }
+        p->n_phases = n_phase;
+        const int n_hot = n_phase * kXcd;                        // hot classes; class index n_hot = cold
+
         // ---- work decomposition ----------------------------------------------------------
         // short rows: several per wavefront; whole rows: one item; long rows: cut at
         // multiples of dist neighbour partitions, item k pairing local run k with remote run k.
-        // Rows with at least xcd_min_deg neighbours are first regrouped by source class (a hash
-        // of the table row id, kXcd classes): each class gets its own items, and the launch order
-        // below hands all items of class c to XCD c, so that each XCD's L2 only has to hold one
-        // eighth of the embedding rows those heavy rows touch.
+        // Rows with at least xcd_min_deg neighbours are first regrouped by source class: each
+        // class with at least min_piece neighbours becomes a piece with its own items (the rest
+        // joins the row's cold piece), and the launch order below hands the items of class
+        // (phase, x) to XCD x, phase by phase.
         const int64_t run = static_cast<int64_t>(ps) * dist;   // neighbours per run
-        const bool use_classes = xcd_min_deg > 0;
         if (use_classes) { p->sched_local_col = p->local_col; p->sched_remote_col = p->remote_col; }
-        std::vector<std::vector<WorkItem>> queue(kXcd);
-        std::vector<int64_t> queue_work(kXcd, 0);
-        std::vector<WorkItem> light;
+        std::vector<std::vector<WorkItem>> bucket(static_cast<size_t>(std::max(n_hot, 1)));   // hot items by class
+        std::vector<WorkItem> cold;                              // cold pieces and whole rows
         std::vector<std::vector<int32_t>> by_len(short_max >= 0 ? short_max + 1 : 0);
         auto item_work = [](const WorkItem &it) { return static_cast<int64_t>(it.lend - it.lbeg) + (it.rend - it.rbeg) + 8; };
-        auto regroup = [](std::vector<int32_t> &col, int32_t b, int32_t e, int32_t (&cut)[kXcd + 1]) {
-            // stable counting sort of col[b, e) by class; cut[c] = start of class c
-            int32_t cnt[kXcd] = {0};
-            for (int32_t i = b; i < e; ++i) ++cnt[source_class(col[i])];
+        std::vector<int32_t> n_in(static_cast<size_t>(n_hot) + 1), lcut(static_cast<size_t>(n_hot) + 2), rcut(static_cast<size_t>(n_hot) + 2), pos(static_cast<size_t>(n_hot) + 1), tmp;
+        std::vector<uint8_t> final_class(static_cast<size_t>(n_hot) + 1);
+        // stable counting sort of col[b, e) by final class of the table row `base + col`; cut[c] = start of class c
+        auto regroup = [&](std::vector<int32_t> &col, int32_t b, int32_t e, int64_t base, std::vector<int32_t> &cut) {
+            std::fill(pos.begin(), pos.end(), 0);
+            for (int32_t i = b; i < e; ++i) ++pos[final_class[std::min<int>(p->src_class[base + col[i]], n_hot)]];
             cut[0] = b;
-            for (int c = 0; c < kXcd; ++c) cut[c + 1] = cut[c] + cnt[c];
-            std::vector<int32_t> tmp(col.begin() + b, col.begin() + e);
-            int32_t pos[kXcd];
-            for (int c = 0; c < kXcd; ++c) pos[c] = cut[c];
-            for (int32_t u : tmp) col[pos[source_class(u)]++] = u;
+            for (int c = 0; c <= n_hot; ++c) cut[c + 1] = cut[c] + pos[c];
+            tmp.assign(col.begin() + b, col.begin() + e);
+            for (int c = 0; c <= n_hot; ++c) pos[c] = cut[c];
+            for (int32_t u : tmp) col[pos[final_class[std::min<int>(p->src_class[base + u], n_hot)]]++] = u;
         };
+        std::vector<std::pair<WorkItem, int>> row_items;         // item, class (n_hot = cold)
         for (int64_t v = 0; v < n_own; ++v) {
             const int32_t l0 = p->local_row_ptr[v], l1 = p->local_row_ptr[v + 1];
             const int32_t r0 = p->remote_row_ptr[v], r1 = p->remote_row_ptr[v + 1];
@@ -252,20 +320,24 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
             p->n_groups_local += ceil_div(dl, ps);
             p->n_groups_remote += ceil_div(dr, ps);
             if (short_max >= 0 && dl + dr <= short_max) { by_len[dl + dr].push_back(static_cast<int32_t>(v)); continue; }
-            // the pieces of this row: one per class if it is regrouped, otherwise the whole row
-            int32_t lcut[kXcd + 1], rcut[kXcd + 1];
-            int n_piece = 1;
-            if (use_classes && dl + dr >= xcd_min_deg) {
-                regroup(p->sched_local_col, l0, l1, lcut);
-                regroup(p->sched_remote_col, r0, r1, rcut);
-                n_piece = kXcd;
+            // the pieces of this row: one per surviving class if it is regrouped, otherwise the whole row
+            int first_piece = n_hot, n_piece_end = n_hot + 1;     // default: only the cold piece = the whole row
+            if (use_classes && n_hot > 0 && dl + dr >= xcd_min_deg) {
+                std::fill(n_in.begin(), n_in.end(), 0);
+                for (int32_t i = l0; i < l1; ++i) ++n_in[std::min<int>(p->src_class[p->local_col[i]], n_hot)];
+                for (int32_t i = r0; i < r1; ++i) ++n_in[std::min<int>(p->src_class[n_own + p->remote_col[i]], n_hot)];
+                for (int c = 0; c < n_hot; ++c) final_class[c] = static_cast<uint8_t>(n_in[c] >= min_piece ? c : n_hot);
+                final_class[n_hot] = static_cast<uint8_t>(n_hot);
+                regroup(p->sched_local_col, l0, l1, 0, lcut);
+                regroup(p->sched_remote_col, r0, r1, n_own, rcut);
+                first_piece = 0;
             } else {
-                lcut[0] = l0; lcut[1] = l1; rcut[0] = r0; rcut[1] = r1;
+                lcut[n_hot] = l0; lcut[n_hot + 1] = l1; rcut[n_hot] = r0; rcut[n_hot + 1] = r1;
             }
-            std::vector<std::pair<WorkItem, int>> row_items;   // item, class (-1 = any XCD)
-            for (int c = 0; c < n_piece; ++c) {
+            row_items.clear();
+            for (int c = first_piece; c < n_piece_end; ++c) {
                 const int64_t pl = lcut[c + 1] - lcut[c], pr = rcut[c + 1] - rcut[c];
-                if (n_piece > 1 && pl + pr == 0) continue;
+                if (pl + pr == 0 && !(c == n_hot && row_items.empty())) continue;   // an empty row still needs its one item
                 const int64_t n_it = std::max<int64_t>(1, std::max(ceil_div(pl, run), ceil_div(pr, run)));
                 for (int64_t k = 0; k < n_it; ++k) {
                     WorkItem it;
@@ -276,7 +348,7 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
                     it.rend = static_cast<int32_t>(std::min<int64_t>(rcut[c] + (k + 1) * run, rcut[c + 1]));
                     it.slot = -1;
                     it.pad0 = it.pad1 = 0;
-                    row_items.emplace_back(it, n_piece > 1 ? c : -1);
+                    row_items.emplace_back(it, c);
                 }
             }
             if (row_items.size() > 1) {                      // partial sums + fix-up
@@ -285,20 +357,27 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
                 for (auto &ri : row_items) ri.first.slot = static_cast<int32_t>(p->n_split_items++);
             }
             for (auto &ri : row_items) {
-                if (ri.second >= 0) { queue[ri.second].push_back(ri.first); queue_work[ri.second] += item_work(ri.first); }
-                else if (ri.first.slot >= 0) p->items.push_back(ri.first);     // cut, not regrouped: heavy, goes first
-                else light.push_back(ri.first);
+                if (ri.second < n_hot) bucket[ri.second].push_back(ri.first);
+                else cold.push_back(ri.first);
             }
         }
+        // heavy items first, so that the tail of the launch is made of small ones
+        std::stable_sort(cold.begin(), cold.end(), [&](const WorkItem &a, const WorkItem &b) { return item_work(a) > item_work(b); });
         if (!use_classes) {
-            p->items.insert(p->items.end(), light.begin(), light.end());
+            p->items = std::move(cold);
         } else {
-            // cut-but-not-regrouped items (none when xcd_min_deg <= ps*dist) and whole-row items fill
-            // the queues so that every XCD gets the same amount of work
-            std::vector<WorkItem> rest;
-            rest.swap(p->items);
-            rest.insert(rest.end(), light.begin(), light.end());
-            for (const WorkItem &it : rest) {
+            // XCD x takes the hot items of classes (0, x), (1, x), ... in that order; cold items then
+            // go, largest first, to whichever XCD has the least work so far (a gather that hits in L2
+            // is taken as half the cost of one that does not)
+            std::vector<std::vector<WorkItem>> queue(kXcd);
+            std::vector<int64_t> queue_work(kXcd, 0);
+            for (int c = 0; c < n_hot; ++c) {
+                std::vector<WorkItem> &q = queue[c % kXcd];
+                for (const WorkItem &it : bucket[c]) queue_work[c % kXcd] += item_work(it);
+                q.insert(q.end(), bucket[c].begin(), bucket[c].end());
+            }
+            for (int c = 0; c < kXcd; ++c) queue_work[c] /= 2;
+            for (const WorkItem &it : cold) {
                 const int c = static_cast<int>(std::min_element(queue_work.begin(), queue_work.end()) - queue_work.begin());
                 queue[c].push_back(it);
                 queue_work[c] += item_work(it);
@@ -340,6 +419,7 @@ mgg_status_t mgg_partition_info(const mgg_partition_t *p, mgg_partition_info_t *
     o->num_parts = p->num_parts; o->part_id = p->part_id;
     o->ps = p->ps; o->dist = p->dist; o->short_max = p->short_max; o->on_device = p->device >= 0;
     o->xcd_min_deg = p->xcd_min_deg; o->wpb = p->wpb;
+    o->hot_rows = p->hot_rows; o->n_phases = p->n_phases; o->min_piece = p->min_piece; o->hot_min_count = p->hot_min_count;
     o->n_groups_local = p->n_groups_local; o->n_groups_remote = p->n_groups_remote;
     o->n_short_rows = static_cast<int64_t>(p->short_rows.size());
     o->n_items = static_cast<int64_t>(p->items.size());
@@ -366,6 +446,14 @@ mgg_status_t mgg_partition_export(const mgg_partition_t *p, mgg_partition_arrays
     copy_out(p->short_rows, a->short_rows);
     copy_out(p->sched_local_col.empty() ? p->local_col : p->sched_local_col, a->sched_local_col);
     copy_out(p->sched_remote_col.empty() ? p->remote_col : p->sched_remote_col, a->sched_remote_col);
+    if (a->src_class_local || a->src_class_halo) {
+        // -1: cold (or no classes at all); otherwise phase * 8 + XCD
+        for (int64_t i = 0; i < p->n_own && a->src_class_local; ++i)
+            a->src_class_local[i] = p->src_class.empty() || p->src_class[i] == kColdClass ? -1 : p->src_class[i];
+        const int64_t nh = static_cast<int64_t>(p->halo_gid.size());
+        for (int64_t i = 0; i < nh && a->src_class_halo; ++i)
+            a->src_class_halo[i] = p->src_class.empty() || p->src_class[p->n_own + i] == kColdClass ? -1 : p->src_class[p->n_own + i];
+    }
     for (size_t i = 0; i < p->items.size(); ++i) {
         const WorkItem &it = p->items[i];
         if (a->item_row) a->item_row[i] = it.row;

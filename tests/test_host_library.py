@@ -42,7 +42,7 @@ def _compare_with_oracle(row_ptr, col, parts, p, bounds, **opts):
         assert np.array_equal(got[f"grp_{kind}_row"], row)
         assert np.array_equal(got[f"grp_{kind}_start"], start)
         assert np.array_equal(got[f"grp_{kind}_end"], end)
-    _check_schedule(got, info)
+    _check_schedule(got, info, hot_by_popularity=opts.get("hot_phases", 0) > 0)
     part.destroy()
     return got, info
 
@@ -51,7 +51,7 @@ def _source_class(x):
     return ((x.astype(np.uint64) * np.uint64(0x9E3779B1)) & np.uint64(0xFFFFFFFF)) >> np.uint64(29)
 
 
-def _check_schedule(got, info):
+def _check_schedule(got, info, hot_by_popularity=True):
     """Several schedules are valid; check that this one covers every neighbour exactly once,
     keeps items within one row and within ps * dist neighbours per list, uses each scratch slot
     once, walks a per-row permutation of the canonical columns, and -- for rows regrouped by
@@ -99,17 +99,58 @@ def _check_schedule(got, info):
         assert np.array_equal(np.sort(row_of * big + canon), np.sort(row_of * big + sched))
     if info.xcd_min_deg > 0:
         assert got["item_row"].size % (8 * info.wpb) == 0                # 8 XCDs x wpb items per workgroup
-        regrouped = deg[rows] >= info.xcd_min_deg
         xcd = (pos // info.wpb) % 8
-        for i in np.nonzero(regrouped)[0][:4000]:
-            cols = np.concatenate([got["sched_local_col"][lbeg[i]:lend[i]], got["sched_remote_col"][rbeg[i]:rend[i]]])
-            assert cols.size and np.all(_source_class(cols) == xcd[i])
-        light = ~regrouped & whole
-        assert np.all(counts[rows[light]] == 1)
+        cl, ch = got["src_class_local"], got["src_class_halo"]
+        n_hot = 8 * info.n_phases
+        assert np.all((cl >= -1) & (cl < n_hot)) and np.all((ch >= -1) & (ch < n_hot))
+        if hot_by_popularity:
+            # classes follow the gather counts: every hot class holds at most hot_rows table rows, no row of
+            # phase p + 1 is gathered more often than a row of phase p, cold rows are the least gathered
+            cnt = np.concatenate([np.bincount(got["local_col"], minlength=n_own),
+                                  np.bincount(got["remote_col"], minlength=info.num_halo)])
+            cls = np.concatenate([cl, ch])
+            if n_hot:
+                assert np.bincount(cls[cls >= 0], minlength=n_hot).max() <= info.hot_rows
+                assert cnt[cls >= 0].min() >= info.hot_min_count
+                lo = [cnt[(cls >= 0) & (cls // 8 == ph)].min() for ph in range(info.n_phases)]
+                hi = [cnt[(cls >= 0) & (cls // 8 == ph)].max() for ph in range(info.n_phases)]
+                assert all(lo[i] >= hi[i + 1] for i in range(info.n_phases - 1))
+                if (cls < 0).any():
+                    assert cnt[cls < 0].max() <= lo[-1]
+                # phase 0 is dealt round-robin: the 8 classes of a phase differ by at most one row
+                sizes = np.bincount(cls[(cls >= 0) & (cls < 8)], minlength=8)
+                assert sizes.max() - sizes.min() <= 1
+        # an item of a regrouped row gathers rows of one class only; a hot item runs on the XCD of its class,
+        # after every item of an earlier phase in that XCD's queue; hot pieces hold at least min_piece neighbours
+        regrouped = np.nonzero(deg[rows] >= info.xcd_min_deg)[0]
+        rng = np.random.default_rng(0)
+        last_phase = np.full(8, -1)
+        piece_size = {}
+        for i in (regrouped if regrouped.size <= 6000 else np.sort(rng.choice(regrouped, 6000, replace=False))):
+            c = np.concatenate([cl[got["sched_local_col"][lbeg[i]:lend[i]]], ch[got["sched_remote_col"][rbeg[i]:rend[i]]]])
+            if c.size == 0:
+                continue
+            r = rows[i]
+            row_cls = np.concatenate([cl[got["local_col"][lrp[r]:lrp[r + 1]]], ch[got["remote_col"][rrp[r]:rrp[r + 1]]]])
+            row_count = np.bincount(row_cls[row_cls >= 0], minlength=max(n_hot, 1))   # neighbours of this row per class
+            hot = c[c >= 0]
+            if hot.size == c.size and np.all(hot == hot[0]) and row_count[hot[0]] >= info.min_piece:
+                assert hot[0] % 8 == xcd[i]
+                assert hot[0] // 8 >= last_phase[xcd[i]]
+                last_phase[xcd[i]] = hot[0] // 8
+                piece_size[(r, hot[0])] = piece_size.get((r, hot[0]), 0) + c.size
+            else:
+                # the row's cold piece: cold rows plus classes too small to stand alone
+                assert np.all(row_count[hot] < info.min_piece)
+        if regrouped.size <= 6000:
+            for (r, h), v in piece_size.items():                         # a hot piece is never cut short
+                row_cls = np.concatenate([cl[got["local_col"][lrp[r]:lrp[r + 1]]], ch[got["remote_col"][rrp[r]:rrp[r + 1]]]])
+                assert v == np.count_nonzero(row_cls == h)
     else:
         assert np.array_equal(got["sched_local_col"], got["local_col"])
         assert np.array_equal(got["sched_remote_col"], got["remote_col"])
         assert np.all(valid)
+        assert np.all(got["src_class_local"] == -1) and np.all(got["src_class_halo"] == -1)
 
 
 def test_partition_matches_hand_written_fixture():
@@ -133,13 +174,15 @@ def test_partition_matches_hand_written_fixture():
                                                      (8, 64, 1, 40), (2, 1, 1, 1)])
 def test_partition_bit_exact_against_oracle(parts, ps, dist, short_max, xcd_min_deg):
     wpb = {-1: 0, 1: 1, 24: 16, 300: 3}[xcd_min_deg]
+    hot = {-1: {}, 1: dict(hot_rows=16, hot_phases=3, min_piece=1, hot_min_count=1),
+           24: dict(hot_rows=40, hot_phases=31, min_piece=3, hot_min_count=2), 300: dict(hot_phases=-1)}[xcd_min_deg]
     rng = np.random.default_rng(parts * 100 + ps)
     row_ptr, col = inputs.rmat_graph(12, 50000, 0.57, 0.19, 0.19, 0.05, rng)
     n = row_ptr.size - 1
     bounds = inputs.equal_node_bounds(n, parts)
     for p in range(parts):
         _compare_with_oracle(row_ptr, col, parts, p, bounds, ps=ps, dist=dist, short_max=short_max,
-                             xcd_min_deg=xcd_min_deg, wpb=wpb)
+                             xcd_min_deg=xcd_min_deg, wpb=wpb, **hot)
 
 
 def test_partition_with_self_loops_duplicates_and_empty_ranges():
