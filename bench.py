@@ -238,6 +238,57 @@ def calibrate_gather(dims=(64, 100, 256), n_halo: int = 1 << 22, per_row: int = 
     return out_lines
 
 
+def run_orders(cfg: int, iters: int = 20):
+    """Whole-layer time (mgg_layer_forward, HIP events on the launch stream) with the aggregation
+    first -- the paper's formulation -- and with the first matrix product first, which gathers
+    rows of the output width instead of the input width."""
+    import torch
+    from paper_2209_06800_amd import binding, inputs
+    dev = "cuda:0"
+    w = inputs.config(cfg)
+    part = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
+    info = part.info
+    hg = part.export()["halo_gid"]
+    nnz = int(info.nnz_local + info.nnz_remote)
+    esz = 2 if w.dtype == "bf16" else 4
+    rows = []
+    xl = xh = None
+    for li, layer in enumerate(w.layers):
+        d_in = layer.dims[0]
+        if li == 0:
+            pad = 128 if (d_in * esz) % 16 else 0
+            xl, xh = to_dev(w.x[w.lb:w.ub], dev, pad), (to_dev(w.x[hg], dev, pad) if hg.size else None)
+        else:
+            xl = out_prev
+            xh = to_dev(inputs.layer2_halo_table(w.notes["layer2_halo_seed"], int(info.num_halo), d_in), dev)
+        ws = [to_dev(m, dev) for m in layer.weights]
+        res = {"layer": li, "dims": layer.dims}
+        for order in ("agg_first", "update_first"):
+            need = binding.mgg_layer_workspace_bytes(part, layer.mode, ws, layer.acts, eps=layer.eps, order=order)
+            wsp = torch.empty(need, dtype=torch.uint8, device=dev)
+            out = torch.empty((int(info.n_own), layer.dims[-1]), dtype=torch.float32, device=dev)
+            for _ in range(3):
+                binding.mgg_layer_forward(part, layer.mode, xl, xh, ws, layer.acts, eps=layer.eps, workspace=wsp, out=out, order=order)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                binding.mgg_layer_forward(part, layer.mode, xl, xh, ws, layer.acts, eps=layer.eps, workspace=wsp, out=out, order=order)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / iters
+            res[order + "_ms"] = round(ms, 4)
+            res[order + "_gedges_per_s"] = round(nnz / ms / 1e6, 3)
+            if order == "agg_first":
+                out_prev = out
+            del wsp
+        res["speedup"] = round(res["agg_first_ms"] / res["update_first_ms"], 3)
+        log(f"[orders] layer {li} {layer.dims}: aggregate first {res['agg_first_ms']} ms, update first {res['update_first_ms']} ms "
+            f"(x{res['speedup']}; includes transforming the {int(info.num_halo)} halo rows on this GPU)")
+        rows.append(res)
+    part.destroy()
+    return {"workload": w.name, "edges": nnz, "n_own": int(info.n_own), "num_halo": int(info.num_halo), "layers": rows}
+
+
 def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 20.0, calibrate_copy: bool = False):
     import torch
     from paper_2209_06800_amd import binding, inputs
@@ -397,6 +448,8 @@ def main():
                     help="run the greedy search over ps / dist / wpb (section 6) on layer 0's aggregation and exit")
     ap.add_argument("--tune-exhaustive", action="store_true",
                     help="like --tune, and measure the whole 150-point grid beside it")
+    ap.add_argument("--compare-orders", action="store_true",
+                    help="time every layer as Update(Aggregate(X)) and as Aggregate(X W) (+ bias, activation) and exit")
     ap.add_argument("--calibrate-gather", action="store_true",
                     help="launch the aggregation kernel on a graph that gathers each of 4 Mi table rows exactly once "
                          "(known L2-miss bytes; reference for rocprofv3 --pmc runs) and exit")
@@ -407,6 +460,9 @@ def main():
         print("bench.py measures one GPU's share on one MI355X; multi-GPU runs are not part of this build "
               "(no collectives, no second GPU). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    if args.compare_orders:
+        print(json.dumps(run_orders(args.config)), flush=True)
+        return
     if args.calibrate_gather:
         print(json.dumps({"calibrate_gather": calibrate_gather()}), flush=True)
         return

@@ -179,6 +179,13 @@ mgg_status_t mgg_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int6
                         mgg_dtype_t w_dtype, const void *w, const float *bias, int32_t d_out,
                         mgg_act_t act, mgg_dtype_t out_dtype, void *out, int64_t ld_out, void *stream);
 
+/* Order of the aggregation and of the first linear of the Update.  Aggregation is linear, so
+ * Aggregate(X) W = Aggregate(X W) (section 7: A-hat X W is one product); when W narrows the rows
+ * the second form gathers d_out-wide rows instead of d_in-wide ones.  Values agree within
+ * rounding.  AUTO takes UPDATE_FIRST when the transformed rows are at most 3/4 the bytes of the
+ * input rows and the combination is supported, AGG_FIRST otherwise. */
+typedef enum { MGG_ORDER_AGG_FIRST = 0, MGG_ORDER_UPDATE_FIRST = 1, MGG_ORDER_AUTO = 2 } mgg_order_t;
+
 /* One GNN layer: Aggregate, then n_linear (1 or 2) Updates (GCN: one; GIN's MLP: two). */
 typedef struct {
     mgg_agg_t   mode;
@@ -189,10 +196,12 @@ typedef struct {
     const void *w[2];          /* DEVICE, [dims[i] x dims[i+1]] row-major */
     const float *bias[2];      /* DEVICE fp32 or NULL */
     mgg_act_t   act[2];
+    mgg_order_t order;         /* 0 = AGG_FIRST, the paper's formulation */
 } mgg_layer_desc_t;
 
 /* Bytes of DEVICE workspace mgg_layer_forward needs (aggregation result and, for two
- * linears, the hidden activations).  Returns 0 on bad arguments. */
+ * linears, the hidden activations; with UPDATE_FIRST the transformed local and halo tables).
+ * Returns 0 on bad arguments. */
 size_t mgg_layer_workspace_bytes(const mgg_partition_t *p, const mgg_layer_desc_t *layer);
 
 /* ---------------------------------------------------------------------------------------
@@ -202,6 +211,11 @@ size_t mgg_layer_workspace_bytes(const mgg_partition_t *p, const mgg_layer_desc_
  * DEVICE buffer of at least mgg_layer_workspace_bytes() bytes, 256-byte aligned.
  * out [n_own x dims[n_linear]] DEVICE, out_dtype F32 or BF16.  With BF16 weights the hidden
  * activations of a 2-linear MLP are kept in bf16.
+ * UPDATE_FIRST: T = X w[0] is computed for the local AND the halo table (fp32, no bias, no
+ * activation), T is aggregated at width dims[1], and bias[0] / act[0] are applied to the
+ * aggregated rows.  Transforming the halo rows here stands in for the GPUs that own them:
+ * in a multi-GPU run each GPU transforms its own rows once and the exchange ships the
+ * narrower rows.  Needs out_dtype F32 when n_linear is 1 (else MGG_ERR_UNSUPPORTED).
  * ------------------------------------------------------------------------------------- */
 mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t *layer,
                                mgg_dtype_t x_dtype, const void *x_local, const void *x_halo, int64_t ld_x,

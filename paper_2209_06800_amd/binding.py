@@ -21,6 +21,8 @@ AGG_GCN_SYM, AGG_GIN_SUM = 0, 1
 ACT_NONE, ACT_RELU = 0, 1
 _MODE = {"gcn": AGG_GCN_SYM, "gin": AGG_GIN_SUM}
 _ACT = {"none": ACT_NONE, "relu": ACT_RELU}
+ORDER_AGG_FIRST, ORDER_UPDATE_FIRST, ORDER_AUTO = 0, 1, 2
+_ORDER = {"agg_first": ORDER_AGG_FIRST, "update_first": ORDER_UPDATE_FIRST, "auto": ORDER_AUTO}
 _STATUS_NAME = ["OK", "INVALID_ARG", "BAD_GRAPH", "UNSUPPORTED", "ALLOC", "HIP"]
 
 EXPORTED_SYMBOLS = [
@@ -80,7 +82,8 @@ class Model(C.Structure):
 
 class LayerDesc(C.Structure):
     _fields_ = [("mode", C.c_int), ("eps", C.c_float), ("n_linear", C.c_int32), ("dims", C.c_int32 * 3),
-                ("w_dtype", C.c_int), ("w", C.c_void_p * 2), ("bias", C.c_void_p * 2), ("act", C.c_int * 2)]
+                ("w_dtype", C.c_int), ("w", C.c_void_p * 2), ("bias", C.c_void_p * 2), ("act", C.c_int * 2),
+                ("order", C.c_int)]
 
 
 _lib = None
@@ -304,8 +307,9 @@ def mgg_update(a, w, bias=None, act: str = "none", *, out=None, out_dtype=None, 
     return out
 
 
-def _layer_desc(mode, eps, weights, biases, acts):
+def _layer_desc(mode, eps, weights, biases, acts, order="agg_first"):
     d = LayerDesc()
+    d.order = _ORDER[order]
     d.mode = _MODE[mode]
     d.eps = eps
     d.n_linear = len(weights)
@@ -321,18 +325,20 @@ def _layer_desc(mode, eps, weights, biases, acts):
     return d
 
 
-def mgg_layer_workspace_bytes(part: Partition, mode, weights, acts, eps: float = 0.0, biases=None) -> int:
-    d = _layer_desc(mode, eps, weights, biases, acts)
+def mgg_layer_workspace_bytes(part: Partition, mode, weights, acts, eps: float = 0.0, biases=None,
+                              order: str = "agg_first") -> int:
+    d = _layer_desc(mode, eps, weights, biases, acts, order)
     return int(lib().mgg_layer_workspace_bytes(part.handle, C.byref(d)))
 
 
 def mgg_layer_forward(part: Partition, mode: str, x_local, x_halo, weights, acts, *, eps: float = 0.0,
-                      biases=None, workspace=None, out=None, out_dtype=None, stream=None):
-    """One layer: Aggregate then 1 or 2 Updates, all enqueued on one stream."""
+                      biases=None, workspace=None, out=None, out_dtype=None, stream=None, order: str = "agg_first"):
+    """One layer: Aggregate then 1 or 2 Updates (or, order="update_first", the first linear before
+    the aggregation), all enqueued on one stream."""
     import torch
     if len(weights) not in (1, 2):
         raise MggError(ERR_INVALID_ARG, "a layer has 1 or 2 linears")
-    d = _layer_desc(mode, eps, weights, biases, acts)
+    d = _layer_desc(mode, eps, weights, biases, acts, order)
     need = int(lib().mgg_layer_workspace_bytes(part.handle, C.byref(d)))
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=x_local.device)

@@ -44,8 +44,11 @@ struct AggArgs {
     int32_t gcn;             // 1: symmetric normalisation, 0: plain sum
     float self_w;            // GIN: 1 + eps
     int32_t out_vec_ok;      // out rows allow VEC-wide stores
+    int32_t out_dim;         // columns of `out` that exist (<= nvec * VEC; the rest of the last vector is padding of the tables)
     int32_t phase;           // 0: local and remote lists in one launch; 1: local lists (+ self term) only;
                              // 2: remote lists only, added to what phase 1 left in out
+    const float *bias;       // optional epilogue of the final value: + bias[column], then ReLU if relu != 0
+    int32_t relu;            // (used when the Update's matrix product was applied before the aggregation)
 };
 
 // ---- element access ---------------------------------------------------------------------
@@ -137,12 +140,30 @@ __device__ __forceinline__ void write_final(const AggArgs &a, const Acc<K> &acc,
             unpack<K::BF16, K::VEC>(*reinterpret_cast<const typename K::raw *>(xs + static_cast<int64_t>(vi) * K::VEC), xv);
             if (a.phase == 2) {                 // second of two launches: add to the first one's result
 #pragma unroll
-                for (int e = 0; e < K::VEC; ++e) r[e] = o[static_cast<int64_t>(vi) * K::VEC + e] + dv * acc.v[c][e];
+                for (int e = 0; e < K::VEC; ++e) r[e] = (vi * K::VEC + e < a.out_dim ? o[vi * K::VEC + e] : 0.f) + dv * acc.v[c][e];
             } else {
 #pragma unroll
                 for (int e = 0; e < K::VEC; ++e) r[e] = dv * (acc.v[c][e] + ws * xv[e]);
             }
-            store_vec<K::VEC>(o + static_cast<int64_t>(vi) * K::VEC, r, a.out_vec_ok);
+            if (a.phase != 1) {                 // the value is final: optional bias and ReLU
+                if (a.bias) {
+#pragma unroll
+                    for (int e = 0; e < K::VEC; ++e)
+                        if (vi * K::VEC + e < a.out_dim) r[e] += a.bias[vi * K::VEC + e];
+                }
+                if (a.relu) {
+#pragma unroll
+                    for (int e = 0; e < K::VEC; ++e) r[e] = fmaxf(r[e], 0.f);
+                }
+            }
+            const int col0 = vi * K::VEC;
+            if (col0 + K::VEC <= a.out_dim) {
+                store_vec<K::VEC>(o + col0, r, a.out_vec_ok);
+            } else {                            // last vector reaches into the padding: store what exists
+#pragma unroll
+                for (int e = 0; e < K::VEC; ++e)
+                    if (col0 + e < a.out_dim) o[col0 + e] = r[e];
+            }
         }
     }
 }
@@ -389,7 +410,7 @@ template <bool BF16>
 __global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_rows, int32_t dim, const float *scratch,
                                                        int64_t scratch_ld, const void *x_local, int64_t ld_x,
                                                        const float *dinv_own, int32_t gcn, float self_w, float *out,
-                                                       int64_t ld_out, int32_t phase)
+                                                       int64_t ld_out, int32_t phase, const float *bias, int32_t relu)
 {
     __shared__ float part[kWavesPerBlock][kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -421,7 +442,12 @@ __global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_row
             else
                 xv = static_cast<const float *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k];
             float *o = out + static_cast<int64_t>(sr.row) * ld_out + k;
-            *o = phase == 2 ? *o + dv * total : dv * (total + ws * xv);
+            float r = phase == 2 ? *o + dv * total : dv * (total + ws * xv);
+            if (phase != 1) {
+                if (bias) r += bias[k];
+                if (relu) r = fmaxf(r, 0.f);
+            }
+            *o = r;
         }
         __syncthreads();
     }
@@ -460,8 +486,9 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 
 mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
                               const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x, float *out,
-                              int64_t ld_out, hipStream_t stream)
+                              int64_t ld_out, hipStream_t stream, const float *bias, mgg_act_t act, int32_t out_dim)
 {
+    if (out_dim <= 0) out_dim = dim;
     const bool bf16 = x_dtype == MGG_BF16;
     const size_t esz = bf16 ? 2 : 4;
     const void *xh = x_halo ? x_halo : x_local;   // never dereferenced when there is no halo
@@ -532,6 +559,9 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
     a.ps = p->ps;
     a.gcn = mode == MGG_AGG_GCN_SYM;
     a.self_w = 1.f + eps;
+    a.bias = bias;
+    a.out_dim = out_dim;
+    a.relu = act == MGG_ACT_RELU;
     const size_t out_bytes = (vec >= 4 ? 4 : vec) * sizeof(float);
     a.out_vec_ok = (ld_out % (vec >= 4 ? 4 : vec) == 0) && aligned(out, out_bytes);
 
@@ -562,11 +592,11 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
         const int32_t n_split = static_cast<int32_t>(p->split_rows.size());
         if (n_split > 0) {
             if (bf16)
-                hipLaunchKernelGGL(fixup_kernel<true>, dim3(n_split), dim3(kBlock), 0, stream, p->d.split_rows, dim,
-                                   p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out, a.phase);
+                hipLaunchKernelGGL(fixup_kernel<true>, dim3(n_split), dim3(kBlock), 0, stream, p->d.split_rows, out_dim,
+                                   p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out, a.phase, bias, a.relu);
             else
-                hipLaunchKernelGGL(fixup_kernel<false>, dim3(n_split), dim3(kBlock), 0, stream, p->d.split_rows, dim,
-                                   p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out, a.phase);
+                hipLaunchKernelGGL(fixup_kernel<false>, dim3(n_split), dim3(kBlock), 0, stream, p->d.split_rows, out_dim,
+                                   p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out, a.phase, bias, a.relu);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return hip_fail(e, "fix-up kernel launch");
         }

@@ -1,4 +1,5 @@
 // Argument checking and composition of the device entry points of libmgg.
+#include <algorithm>
 #include <atomic>
 #include <cstring>
 
@@ -54,19 +55,34 @@ static mgg_status_t check_update(int64_t n_rows, mgg_dtype_t a_dtype, const void
 }
 
 struct LayerPlan {
+    bool update_first = false;
     int64_t ld_agg = 0, ld_hid = 0;
-    size_t agg_bytes = 0, hid_bytes = 0;
+    size_t agg_bytes = 0, hid_bytes = 0;        // aggregation result (width dims[0], or dims[1] when update_first), hidden activations
+    size_t t_local_bytes = 0, t_halo_bytes = 0; // update_first: X w[0] of the two tables, leading dimension ld_agg
     mgg_dtype_t hid_dtype = MGG_F32;
+    size_t total() const { return agg_bytes + hid_bytes + t_local_bytes + t_halo_bytes; }
 };
 
-static bool plan_layer(const mgg_partition *p, const mgg_layer_desc_t *l, LayerPlan *pl)
+static bool plan_layer(const mgg_partition *p, const mgg_layer_desc_t *l, mgg_dtype_t x_dtype, mgg_dtype_t out_dtype, LayerPlan *pl)
 {
     if (!p || !l || (l->n_linear != 1 && l->n_linear != 2)) return false;
     for (int i = 0; i <= l->n_linear; ++i)
         if (l->dims[i] < 1) return false;
-    pl->ld_agg = static_cast<int64_t>(round_up(static_cast<size_t>(l->dims[0]), 8));      // rows start 32-byte aligned
+    if (l->order != MGG_ORDER_AGG_FIRST && l->order != MGG_ORDER_UPDATE_FIRST && l->order != MGG_ORDER_AUTO) return false;
+    // fp32 weights cannot take bf16 input, and a single linear hands its rows straight to `out`
+    const bool supported = !(l->w_dtype == MGG_F32 && x_dtype == MGG_BF16) && (l->n_linear == 2 || out_dtype == MGG_F32);
+    const int64_t in_bytes = static_cast<int64_t>(l->dims[0]) * (x_dtype == MGG_BF16 ? 2 : 4);
+    pl->update_first = l->order == MGG_ORDER_UPDATE_FIRST ||
+                       (l->order == MGG_ORDER_AUTO && supported && static_cast<int64_t>(l->dims[1]) * 4 * 4 <= in_bytes * 3);
+    const int32_t agg_dim = pl->update_first ? l->dims[1] : l->dims[0];
+    pl->ld_agg = static_cast<int64_t>(round_up(static_cast<size_t>(agg_dim), 8));      // rows start 32-byte aligned
     pl->agg_bytes = round_up(static_cast<size_t>(p->n_own) * pl->ld_agg * sizeof(float), 256);
-    if (l->n_linear == 2) {
+    if (pl->update_first) {
+        pl->t_local_bytes = pl->agg_bytes;
+        pl->t_halo_bytes = round_up(p->halo_gid.size() * static_cast<size_t>(pl->ld_agg) * sizeof(float), 256);
+        if (l->n_linear == 1) pl->agg_bytes = 0;       // aggregated rows are the layer's output
+    }
+    if (l->n_linear == 2 && !pl->update_first) {
         pl->hid_dtype = l->w_dtype == MGG_BF16 ? MGG_BF16 : MGG_F32;
         pl->ld_hid = static_cast<int64_t>(round_up(static_cast<size_t>(l->dims[1]), 8));
         pl->hid_bytes = round_up(static_cast<size_t>(p->n_own) * pl->ld_hid * (pl->hid_dtype == MGG_BF16 ? 2 : 4), 256);
@@ -102,9 +118,15 @@ mgg_status_t mgg_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int6
 
 size_t mgg_layer_workspace_bytes(const mgg_partition_t *p, const mgg_layer_desc_t *layer)
 {
-    LayerPlan pl;
-    if (!plan_layer(p, layer, &pl)) return 0;
-    return pl.agg_bytes + pl.hid_bytes + 256;
+    // the largest need over the dtypes the call may be given (UPDATE_FIRST under AUTO depends on them)
+    size_t need = 0;
+    for (mgg_dtype_t xd : {MGG_F32, MGG_BF16})
+        for (mgg_dtype_t od : {MGG_F32, MGG_BF16}) {
+            LayerPlan pl;
+            if (!plan_layer(p, layer, xd, od, &pl)) return 0;
+            need = std::max(need, pl.total());
+        }
+    return need + 256;
 }
 
 mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t *layer, mgg_dtype_t x_dtype,
@@ -112,15 +134,55 @@ mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t 
                                size_t workspace_bytes, mgg_dtype_t out_dtype, void *out, int64_t ld_out, void *stream)
 {
     LayerPlan pl;
-    if (!plan_layer(p, layer, &pl)) return fail(MGG_ERR_INVALID_ARG, "bad layer description");
+    if (!dtype_ok(x_dtype) || !dtype_ok(out_dtype)) return fail(MGG_ERR_INVALID_ARG, "unknown dtype");
+    if (!plan_layer(p, layer, x_dtype, out_dtype, &pl)) return fail(MGG_ERR_INVALID_ARG, "bad layer description");
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return fail(MGG_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
-    if (workspace_bytes < pl.agg_bytes + pl.hid_bytes) return fail(MGG_ERR_INVALID_ARG, "workspace too small: %zu < %zu", workspace_bytes, pl.agg_bytes + pl.hid_bytes);
+    if (workspace_bytes < pl.total()) return fail(MGG_ERR_INVALID_ARG, "workspace too small: %zu < %zu", workspace_bytes, pl.total());
+    const int32_t d0 = layer->dims[0], d1 = layer->dims[1], d2 = layer->dims[2];
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t n_halo = static_cast<int64_t>(p->halo_gid.size());
+    mgg_status_t s;
+
+    if (pl.update_first) {
+        // Aggregate(X) w[0] computed as Aggregate(X w[0]): transform both tables, gather the narrower rows
+        if (layer->n_linear == 1 && out_dtype != MGG_F32) return fail(MGG_ERR_UNSUPPORTED, "UPDATE_FIRST with one linear needs fp32 output");
+        char *ws = static_cast<char *>(workspace);
+        float *t_local = reinterpret_cast<float *>(ws);
+        float *t_halo = reinterpret_cast<float *>(ws + pl.t_local_bytes);
+        float *agg = layer->n_linear == 1 ? static_cast<float *>(out) : reinterpret_cast<float *>(ws + pl.t_local_bytes + pl.t_halo_bytes);
+        const int64_t ld_aggout = layer->n_linear == 1 ? ld_out : pl.ld_agg;
+        if (layer->n_linear == 1 && ld_out < d1) return fail(MGG_ERR_INVALID_ARG, "ld_out %lld < %d", (long long)ld_out, d1);
+        // validate everything before the first launch so that an error leaves no partial output
+        if (n_halo > 0 && !x_halo) return fail(MGG_ERR_INVALID_ARG, "x_halo is NULL but the partition has %lld halo rows", (long long)n_halo);
+        if (ld_x < d0) return fail(MGG_ERR_INVALID_ARG, "ld_x %lld < %d", (long long)ld_x, d0);
+        s = check_aggregate(p, layer->mode, MGG_F32, t_local, t_halo, d1, pl.ld_agg, agg, ld_aggout);
+        if (s == MGG_OK) s = check_update(p->n_own, x_dtype, x_local, ld_x, d0, layer->w_dtype, layer->w[0], d1, MGG_ACT_NONE, MGG_F32, t_local, pl.ld_agg);
+        if (s == MGG_OK && n_halo > 0) s = check_update(n_halo, x_dtype, x_halo, ld_x, d0, layer->w_dtype, layer->w[0], d1, MGG_ACT_NONE, MGG_F32, t_halo, pl.ld_agg);
+        if (s == MGG_OK && layer->n_linear == 2)
+            s = check_update(p->n_own, MGG_F32, agg, pl.ld_agg, d1, layer->w_dtype, layer->w[1], d2, layer->act[1], out_dtype, out, ld_out);
+        if (s == MGG_OK && layer->act[0] != MGG_ACT_NONE && layer->act[0] != MGG_ACT_RELU) s = fail(MGG_ERR_INVALID_ARG, "unknown activation");
+        if (s != MGG_OK) return s;
+        if (p->n_own == 0) return MGG_OK;
+        s = launch_update(p->n_own, x_dtype, x_local, ld_x, d0, layer->w_dtype, layer->w[0], nullptr, d1, MGG_ACT_NONE, MGG_F32, t_local, pl.ld_agg, st);
+        if (s != MGG_OK) return s;
+        if (n_halo > 0) {
+            s = launch_update(n_halo, x_dtype, x_halo, ld_x, d0, layer->w_dtype, layer->w[0], nullptr, d1, MGG_ACT_NONE, MGG_F32, t_halo, pl.ld_agg, st);
+            if (s != MGG_OK) return s;
+        }
+        // the transformed tables are gathered at their width rounded up to whole 16-byte vectors (the
+        // padding columns hold whatever the workspace held and only reach output columns that do not exist)
+        const int32_t d1_padded = static_cast<int32_t>(std::min<int64_t>(round_up(static_cast<size_t>(d1), 4), pl.ld_agg));
+        s = launch_aggregate(p, layer->mode, layer->eps, MGG_F32, t_local, n_halo > 0 ? t_halo : nullptr, d1_padded, pl.ld_agg, agg,
+                             ld_aggout, st, layer->bias[0], layer->act[0], d1);
+        if (s != MGG_OK || layer->n_linear == 1) return s;
+        return launch_update(p->n_own, MGG_F32, agg, pl.ld_agg, d1, layer->w_dtype, layer->w[1], layer->bias[1], d2, layer->act[1],
+                             out_dtype, out, ld_out, st);
+    }
+
     float *agg = static_cast<float *>(workspace);
     void *hid = static_cast<char *>(workspace) + pl.agg_bytes;
-    const int32_t d0 = layer->dims[0], d1 = layer->dims[1], d2 = layer->dims[2];
-
     // validate everything before the first launch so that an error leaves no partial output
-    mgg_status_t s = check_aggregate(p, layer->mode, x_dtype, x_local, x_halo, d0, ld_x, agg, pl.ld_agg);
+    s = check_aggregate(p, layer->mode, x_dtype, x_local, x_halo, d0, ld_x, agg, pl.ld_agg);
     if (s != MGG_OK) return s;
     if (layer->n_linear == 1)
         s = check_update(p->n_own, MGG_F32, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], d1, layer->act[0], out_dtype, out, ld_out);
@@ -132,7 +194,6 @@ mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t 
     if (s != MGG_OK) return s;
     if (p->n_own == 0) return MGG_OK;
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
     s = launch_aggregate(p, layer->mode, layer->eps, x_dtype, x_local, x_halo, d0, ld_x, agg, pl.ld_agg, st);
     if (s != MGG_OK) return s;
     if (layer->n_linear == 1)

@@ -324,7 +324,7 @@ def test_update_bf16(n_rows, d_in, d_out, a_is_bf16):
 SHRINK = {1: 0, 2: 5, 3: 7, 4: 4, 5: 6}
 
 
-def run_config_layers(w: inputs.Workload, rows=None):
+def run_config_layers(w: inputs.Workload, rows=None, order="agg_first"):
     """Forward of every layer of a workload on the GPU and in the oracle; returns max errors."""
     ref_part = oracle.build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
     lb, ub, hg = ref_part["lb"], ref_part["ub"], ref_part["halo_gid"]
@@ -341,7 +341,7 @@ def run_config_layers(w: inputs.Workload, rows=None):
             x_local = h_gpu_np                                   # what the GPU produced for layer 1
             d_x_local, d_x_halo = h_gpu, to_dev(x_halo)
         dw = [to_dev(m) for m in layer.weights]
-        h_gpu = binding.mgg_layer_forward(part, layer.mode, d_x_local, d_x_halo, dw, layer.acts, eps=layer.eps)
+        h_gpu = binding.mgg_layer_forward(part, layer.mode, d_x_local, d_x_halo, dw, layer.acts, eps=layer.eps, order=order)
         torch.cuda.synchronize()
         h_gpu_np = h_gpu.float().cpu().numpy()
         ref = oracle.layer_forward(w.row_ptr, w.col, layer.mode, x_local, layer.weights, layer.acts, eps=layer.eps,
@@ -350,6 +350,13 @@ def run_config_layers(w: inputs.Workload, rows=None):
         agg = oracle.aggregate(w.row_ptr, w.col, layer.mode, x_local, lb=lb, ub=ub, x_halo=x_halo, halo_gid=hg,
                                eps=layer.eps, rows=rows)
         s = np.abs(agg)
+        if order != "agg_first":
+            # the product with the first matrix may run before the aggregation: rounding errors then scale
+            # with sum_u |w_uv| (|x_u| @ |W|) instead of |sum_u w_uv x_u| @ |W|
+            xa_l = np.abs(inputs.bf16_bits_to_f32(x_local)) if x_local.dtype == np.uint16 else np.abs(x_local)
+            xa_h = np.abs(inputs.bf16_bits_to_f32(x_halo)) if x_halo.dtype == np.uint16 else np.abs(x_halo)
+            s = oracle.aggregate(w.row_ptr, w.col, layer.mode, xa_l, lb=lb, ub=ub, x_halo=xa_h, halo_gid=hg,
+                                 eps=abs(layer.eps), rows=rows)
         for m in layer.weights:
             s = s @ np.abs(oracle.to_f64(m))
         k = max(layer.dims[:-1])
@@ -455,3 +462,52 @@ def test_full_size_workloads_sampled_rows_and_checksum(cfg):
     part.destroy()
     del out
     run_config_layers(w, rows=sample)
+
+
+# ----------------------------------------------------------------------------- Update before Aggregate
+@pytest.mark.parametrize("cfg", [4, 5])
+@pytest.mark.parametrize("order", ["update_first", "auto"])
+def test_update_first_order_on_the_narrowing_configs(cfg, order):
+    """Aggregate(X) W = Aggregate(X W) (section 7 writes the layer as one product A-hat X W):
+    configs 4 (602 -> 256) and 5 (100 -> 256 -> 47) through the reordered path."""
+    run_config_layers(inputs.config(cfg, shrink=SHRINK[cfg]), order=order)
+
+
+@pytest.mark.parametrize("mode,bf16,dims,acts,with_bias", [
+    ("gcn", False, (64, 47), ("relu",), True), ("gcn", False, (100, 5), ("none",), True),
+    ("gin", False, (96, 32, 17), ("relu", "none"), True), ("gin", True, (128, 64, 130), ("relu", "relu"), False),
+    ("gcn", True, (136, 24), ("relu",), False), ("gcn", False, (33, 64), ("relu",), True)])
+def test_update_first_matches_the_oracle(mode, bf16, dims, acts, with_bias):
+    row_ptr, col, rng = small_rmat(seed=5)
+    n = row_ptr.size - 1
+    bounds = inputs.equal_node_bounds(n, 3)
+    x = rng.standard_normal((n, dims[0])).astype(np.float32)
+    weights = [(0.1 * rng.standard_normal((dims[i], dims[i + 1]))).astype(np.float32) for i in range(len(dims) - 1)]
+    biases = [rng.standard_normal(dims[i + 1]).astype(np.float32) if with_bias else None for i in range(len(dims) - 1)]
+    if bf16:
+        x, weights = inputs.to_bf16_bits(x), [inputs.to_bf16_bits(m) for m in weights]
+    for p in range(3):
+        ref_part = oracle.build_partition(row_ptr, col, 3, p, bounds)
+        lb, ub, hg = ref_part["lb"], ref_part["ub"], ref_part["halo_gid"]
+        part = binding.mgg_build_partition(row_ptr, col, 3, p, bounds, xcd_min_deg=30)
+        d_b = [None if b is None else to_dev(b) for b in biases]
+        got = {}
+        for order in ("agg_first", "update_first"):
+            # an output view with padded rows checks that nothing is written beyond the last column
+            buf = torch.full((ub - lb, dims[-1] + 3), float("nan"), dtype=torch.float32, device=DEV)
+            out = binding.mgg_layer_forward(part, mode, to_dev(x[lb:ub]), to_dev(x[hg]) if hg.size else None,
+                                            [to_dev(m) for m in weights], acts, eps=0.25, biases=d_b, out=buf[:, :dims[-1]],
+                                            order=order)
+            torch.cuda.synchronize()
+            assert torch.isnan(buf[:, dims[-1]:]).all()
+            got[order] = to_host64(out)
+        ref = oracle.layer_forward(row_ptr, col, mode, x[lb:ub], weights, acts, eps=0.25, lb=lb, ub=ub, x_halo=x[hg],
+                                   halo_gid=hg, biases=biases)
+        xa = np.abs(inputs.bf16_bits_to_f32(x)) if bf16 else np.abs(x)
+        s = oracle.aggregate(row_ptr, col, mode, xa[lb:ub], lb=lb, ub=ub, x_halo=xa[hg], halo_gid=hg, eps=0.25)
+        for i, m in enumerate(weights):
+            s = s @ np.abs(oracle.to_f64(m)) + (0 if biases[i] is None else np.abs(biases[i]))
+        bound = (2.0 ** -6) * s if bf16 else 2e-6 * s + 2.0 * max(dims[:-1]) * 2.0 ** -24 * s
+        for order in got:
+            assert_close(got[order], ref, 2e-2 if bf16 else 1e-4, bound, f"{mode} {dims} part {p} {order}")
+        part.destroy()

@@ -273,3 +273,31 @@ def test_options_round_trip():
         assert binding.mgg_get_option("col_slab_bytes") == v
     for bad in (-1, 3, 96, 8192):
         assert _status(binding.mgg_set_option, "col_slab_bytes", bad) == binding.ERR_INVALID_ARG
+
+
+def test_layer_workspace_bytes_follow_the_order():
+    """Host-side planning of mgg_layer_forward: the aggregate-first form needs the aggregation
+    result (and the hidden activations of a 2-linear MLP); the update-first form needs the two
+    transformed tables instead.  No GPU is touched: the weight pointers are never dereferenced."""
+    rng = np.random.default_rng(3)
+    row_ptr, col = inputs.rmat_graph(10, 8000, 0.57, 0.19, 0.19, 0.05, rng)
+    part = binding.mgg_build_partition(row_ptr, col, 2, 0, None, host_only=True)
+    n, h = part.info.n_own, part.info.num_halo
+    lib = binding.lib()
+
+    def need(dims, order, w_dtype=binding.F32):
+        d = binding.LayerDesc()
+        d.mode, d.n_linear, d.w_dtype, d.order = binding.AGG_GCN_SYM, len(dims) - 1, w_dtype, order
+        for i, v in enumerate(dims):
+            d.dims[i] = v
+        return int(lib.mgg_layer_workspace_bytes(part.handle, ctypes.byref(d)))
+
+    r256 = lambda v: -(-v // 256) * 256
+    assert need((100, 40), binding.ORDER_AGG_FIRST) == r256(n * 104 * 4) + 256
+    assert need((100, 40), binding.ORDER_UPDATE_FIRST) == r256(n * 40 * 4) + r256(h * 40 * 4) + 256
+    assert need((100, 40, 7), binding.ORDER_AGG_FIRST) == r256(n * 104 * 4) + r256(n * 40 * 4) + 256
+    assert need((100, 40, 7), binding.ORDER_UPDATE_FIRST) == 2 * r256(n * 40 * 4) + r256(h * 40 * 4) + 256
+    # AUTO reorders when the transformed rows are at most 3/4 of the input bytes: 40 * 4 <= 0.75 * 100 * 4
+    assert need((100, 40), binding.ORDER_AUTO) == max(need((100, 40), binding.ORDER_AGG_FIRST), need((100, 40), binding.ORDER_UPDATE_FIRST))
+    assert need((100, 90), binding.ORDER_AUTO) == need((100, 90), binding.ORDER_AGG_FIRST)
+    assert need((100, 40), 7) == 0 and need((100, 0), 0) == 0 and need((100,), 0) == 0
