@@ -11,10 +11,12 @@ static std::atomic<int32_t> g_xcd_remap{0};
 static std::atomic<int32_t> g_lds_halo{0};
 static std::atomic<int32_t> g_col_slab_bytes{0};
 static std::atomic<int32_t> g_split_phases{0};
+static std::atomic<int32_t> g_update_stream{1};
 int32_t option_xcd_remap() { return g_xcd_remap.load(); }
 int32_t option_lds_halo() { return g_lds_halo.load(); }
 int32_t option_col_slab_bytes() { return g_col_slab_bytes.load(); }
 int32_t option_split_phases() { return g_split_phases.load(); }
+int32_t option_update_stream() { return g_update_stream.load(); }
 
 static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline bool dtype_ok(mgg_dtype_t t) { return t == MGG_F32 || t == MGG_BF16; }
@@ -219,6 +221,7 @@ mgg_status_t mgg_set_option(const char *key, int32_t value)
     if (!std::strcmp(key, "xcd_remap")) { g_xcd_remap = value; return MGG_OK; }
     if (!std::strcmp(key, "lds_halo")) { g_lds_halo = value; return MGG_OK; }
     if (!std::strcmp(key, "split_phases")) { g_split_phases = value; return MGG_OK; }
+    if (!std::strcmp(key, "update_stream")) { g_update_stream = value; return MGG_OK; }
     return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
 }
 
@@ -229,6 +232,7 @@ mgg_status_t mgg_get_option(const char *key, int32_t *value)
     if (!std::strcmp(key, "lds_halo")) { *value = g_lds_halo; return MGG_OK; }
     if (!std::strcmp(key, "col_slab_bytes")) { *value = g_col_slab_bytes; return MGG_OK; }
     if (!std::strcmp(key, "split_phases")) { *value = g_split_phases; return MGG_OK; }
+    if (!std::strcmp(key, "update_stream")) { *value = g_update_stream; return MGG_OK; }
     return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
 }
 

@@ -92,6 +92,7 @@ int32_t option_xcd_remap();
 int32_t option_lds_halo();
 int32_t option_col_slab_bytes();
 int32_t option_split_phases();
+int32_t option_update_stream();
 
 // kernels (aggregate.hip / update.hip)
 mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,

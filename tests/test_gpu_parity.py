@@ -320,6 +320,41 @@ def test_update_bf16(n_rows, d_in, d_out, a_is_bf16):
         assert_close(to_host64(got), ref, 2e-2, s_bound, f"update bf16 {n_rows}x{d_in}x{d_out} a_bf16={a_is_bf16}")
 
 
+@pytest.mark.parametrize("n_rows,d_in,d_out,w_bf16,a_bf16,out_bf16", [
+    (1000, 64, 64, False, False, False), (33, 32, 128, False, False, False), (4097, 256, 47, False, False, False),
+    (70000, 128, 100, False, False, False), (515, 128, 128, True, False, True), (515, 128, 128, True, True, False),
+    (31, 64, 40, True, True, True), (2049, 256, 96, True, False, False), (300, 64, 128, True, True, True)])
+def test_update_whole_line_kernels(n_rows, d_in, d_out, w_bf16, a_bf16, out_bf16):
+    """Shapes the whole-line kernels cover (whole K slabs, 33..128 output columns): against the
+    oracle, and bit for bit against the register-resident kernels, which contract in the same order;
+    the output view has padded rows so that a store past the last column would be seen."""
+    rng = np.random.default_rng(n_rows + d_in)
+    a = rng.standard_normal((n_rows, d_in)).astype(np.float32)
+    w = (0.1 * rng.standard_normal((d_in, d_out))).astype(np.float32)
+    b = rng.standard_normal(d_out).astype(np.float32)
+    a_in = inputs.to_bf16_bits(a) if a_bf16 else a
+    w_in = inputs.to_bf16_bits(w) if w_bf16 else w
+    ref = oracle.update(a_in, w_in, b, "relu")         # the oracle takes the inputs as given and rounds nothing
+    s_bound = np.abs(oracle.to_f64(a_in)) @ np.abs(oracle.to_f64(w_in)) + np.abs(b)
+    got = {}
+    for stream in (1, 0):
+        binding.mgg_set_option("update_stream", stream)
+        try:
+            pad = 8 if out_bf16 else 4
+            buf = torch.full((n_rows, d_out + pad), float("nan"), dtype=torch.bfloat16 if out_bf16 else torch.float32, device=DEV)
+            out = binding.mgg_update(to_dev(a_in), to_dev(w_in), to_dev(b), "relu", out=buf[:, :d_out])
+            torch.cuda.synchronize()
+        finally:
+            binding.mgg_set_option("update_stream", 1)
+        assert torch.isnan(buf[:, d_out:]).all()
+        got[stream] = out
+        if w_bf16:
+            assert_close(to_host64(out), ref, 2e-2, 2.0 ** -7 * s_bound, f"stream={stream}")
+        else:
+            assert_close(to_host64(out), ref, 1e-4, 2.0 * d_in * 2.0 ** -24 * s_bound, f"stream={stream}")
+    assert torch.equal(got[0], got[1])
+
+
 # ----------------------------------------------------------------------------- whole layers on the five configs
 SHRINK = {1: 0, 2: 5, 3: 7, 4: 4, 5: 6}
 
