@@ -155,8 +155,11 @@ void         mgg_partition_destroy(mgg_partition_t *p);   /* NULL is allowed */
  *
  * x_local [n_own x dim] holds the rows this GPU owns, x_halo [num_halo x dim] the rows of
  * the halo list in halo_gid order (may be NULL iff num_halo == 0); both DEVICE, same dtype
- * and leading dimension ld_x >= dim.  out [n_own x dim] is DEVICE fp32, ld_out >= dim,
- * fully overwritten; it must not alias the inputs.  Accumulation is fp32.
+ * and leading dimension ld_x >= dim.  Both tables must be allocated as rows x ld_x elements:
+ * when ld_x leaves room, rows are read up to the next multiple of 16 bytes (whatever the
+ * padding holds is never used), so that a width like 602 or 47 still gets 16-byte loads.
+ * out [n_own x dim] is DEVICE fp32, ld_out >= dim, fully overwritten (columns >= dim of a
+ * padded out are not touched); it must not alias the inputs.  Accumulation is fp32.
  * The first call with a larger dim than any before grows the partition's scratch buffer
  * (a synchronising device allocation); later calls allocate nothing.
  * Errors: INVALID_ARG (NULL, dim < 1, ld < dim, host-only partition), HIP, ALLOC.

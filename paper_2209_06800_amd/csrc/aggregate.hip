@@ -488,17 +488,20 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
                               const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x, float *out,
                               int64_t ld_out, hipStream_t stream, const float *bias, mgg_act_t act, int32_t out_dim)
 {
-    if (out_dim <= 0) out_dim = dim;
     const bool bf16 = x_dtype == MGG_BF16;
     const size_t esz = bf16 ? 2 : 4;
     const void *xh = x_halo ? x_halo : x_local;   // never dereferenced when there is no halo
 
-    // widest vector the layout allows: it must divide dim and keep every row start aligned
+    // Widest vector the layout allows: it must keep every row start aligned, and the row must hold a
+    // whole number of vectors -- counting the padding between dim and ld_x, which is read (its
+    // values only reach output columns that do not exist) and never written.
+    if (out_dim <= 0) out_dim = dim;
     int vec = 1;
     const int cand[3] = {bf16 ? 8 : 4, 2, 1};
     for (int c : cand) {
         const size_t bytes = c * esz;
-        if (dim % c == 0 && ld_x % c == 0 && aligned(x_local, bytes) && aligned(xh, bytes)) { vec = c; break; }
+        const int64_t padded = (static_cast<int64_t>(dim) + c - 1) / c * c;
+        if (padded <= ld_x && ld_x % c == 0 && aligned(x_local, bytes) && aligned(xh, bytes)) { vec = c; dim = static_cast<int32_t>(padded); break; }
     }
     const int nvec = dim / vec;
     // Column slabs: when one XCD's share of the table rows does not fit its L2 at full width, the

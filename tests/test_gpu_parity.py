@@ -63,7 +63,9 @@ def check_aggregate(w_row_ptr, w_col, parts, part_id, bounds, x, mode, eps=0.0, 
         """Device copy with optional row padding and a base pointer that is not 16-byte aligned."""
         t = to_dev(a)
         if ld_pad or misalign:
-            buf = torch.zeros(a.shape[0] * (dim + ld_pad) + misalign, dtype=t.dtype, device=DEV)
+            # NaN in the padding: the kernel may read it (rows are read in whole 16-byte vectors when
+            # the leading dimension leaves room) but nothing of it may reach the output
+            buf = torch.full((a.shape[0] * (dim + ld_pad) + misalign,), float("nan"), dtype=t.dtype, device=DEV)
             view = buf[misalign:].view(a.shape[0], dim + ld_pad)[:, :dim]
             view.copy_(t)
             return view
