@@ -43,7 +43,9 @@ typedef enum { MGG_F32 = 0, MGG_BF16 = 1 } mgg_dtype_t;
  *          D~^-1/2 (A+I) D~^-1/2 with d~ = (whole-graph degree) + 1.
  * GIN_SUM: section 7, GIN equation: (1+eps) h_v + sum_{u in N(v)} h_u.            */
 typedef enum { MGG_AGG_GCN_SYM = 0, MGG_AGG_GIN_SUM = 1 } mgg_agg_t;
-typedef enum { MGG_ACT_NONE = 0, MGG_ACT_RELU = 1 } mgg_act_t;
+/* SOFTMAX: over each output row, exp(z_j) / sum_k exp(z_k) -- the last step of the 2-layer GCN of
+ * section 7, Z = softmax(A-hat ReLU(A-hat X W0) W1).  Runs as a second, in-place pass over out. */
+typedef enum { MGG_ACT_NONE = 0, MGG_ACT_RELU = 1, MGG_ACT_SOFTMAX = 2 } mgg_act_t;
 
 typedef struct mgg_partition mgg_partition_t;   /* opaque, library-owned */
 

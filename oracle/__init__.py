@@ -24,7 +24,7 @@ F32, BF16, F64 = 0, 1, 2
 GCN, GIN = 0, 1
 ACT_NONE, ACT_RELU = 0, 1
 _MODE = {"gcn": GCN, "gin": GIN}
-_ACT = {"none": ACT_NONE, "relu": ACT_RELU}
+_ACT = {"none": ACT_NONE, "relu": ACT_RELU, "softmax": 2}
 
 
 def build(force: bool = False) -> str:

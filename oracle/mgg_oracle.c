@@ -36,7 +36,7 @@
 
 enum { ORA_F32 = 0, ORA_BF16 = 1, ORA_F64 = 2 };
 enum { ORA_GCN = 0, ORA_GIN = 1 };
-enum { ORA_ACT_NONE = 0, ORA_ACT_RELU = 1 };
+enum { ORA_ACT_NONE = 0, ORA_ACT_RELU = 1, ORA_ACT_SOFTMAX = 2 };
 
 int mgg_oracle_num_threads(void)
 {
@@ -294,7 +294,10 @@ int mgg_oracle_aggregate(int64_t n, const int64_t *row_ptr, const int32_t *col,
 /* ------------------------------------------------------------------------- *
  * Update (section 1: "a fully-connected NN layer"; section 7: X W, ReLU, MLP):
  *     out[i][j] = act( bias[j] + sum_k a[i][k] * w[k][j] )
- * a, w, bias (nullable), out are double, row-major.
+ * a, w, bias (nullable), out are double, row-major.  act = softmax is the last step of the
+ * 2-layer GCN of section 7, Z = softmax(A_hat ReLU(A_hat X W0) W1), taken over each row:
+ * softmax(z)_j = exp(z_j) / sum_k exp(z_k), evaluated as exp(z_j - max z) / sum_k exp(z_k - max z),
+ * which is the same number and cannot overflow.
  * ------------------------------------------------------------------------- */
 int mgg_oracle_update(int64_t n_rows, const double *a, int64_t ld_a, int32_t d_in,
                       const double *w, const double *bias, int32_t d_out, int32_t act,
@@ -312,6 +315,12 @@ int mgg_oracle_update(int64_t n_rows, const double *a, int64_t ld_a, int32_t d_i
         }
         if (act == ORA_ACT_RELU)
             for (int32_t j = 0; j < d_out; ++j) if (o[j] < 0.0) o[j] = 0.0;
+        if (act == ORA_ACT_SOFTMAX) {
+            double zmax = o[0], sum = 0.0;
+            for (int32_t j = 1; j < d_out; ++j) if (o[j] > zmax) zmax = o[j];
+            for (int32_t j = 0; j < d_out; ++j) { o[j] = exp(o[j] - zmax); sum += o[j]; }
+            for (int32_t j = 0; j < d_out; ++j) o[j] /= sum;
+        }
     }
     return 0;
 }

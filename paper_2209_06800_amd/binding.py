@@ -18,9 +18,9 @@ LIB_PATH = os.path.join(_HERE, "libmgg.so")
 OK, ERR_INVALID_ARG, ERR_BAD_GRAPH, ERR_UNSUPPORTED, ERR_ALLOC, ERR_HIP = range(6)
 F32, BF16 = 0, 1
 AGG_GCN_SYM, AGG_GIN_SUM = 0, 1
-ACT_NONE, ACT_RELU = 0, 1
+ACT_NONE, ACT_RELU, ACT_SOFTMAX = 0, 1, 2
 _MODE = {"gcn": AGG_GCN_SYM, "gin": AGG_GIN_SUM}
-_ACT = {"none": ACT_NONE, "relu": ACT_RELU}
+_ACT = {"none": ACT_NONE, "relu": ACT_RELU, "softmax": ACT_SOFTMAX}
 ORDER_AGG_FIRST, ORDER_UPDATE_FIRST, ORDER_AUTO = 0, 1, 2
 _ORDER = {"agg_first": ORDER_AGG_FIRST, "update_first": ORDER_UPDATE_FIRST, "auto": ORDER_AUTO}
 _STATUS_NAME = ["OK", "INVALID_ARG", "BAD_GRAPH", "UNSUPPORTED", "ALLOC", "HIP"]

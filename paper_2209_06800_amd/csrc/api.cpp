@@ -47,7 +47,7 @@ static mgg_status_t check_update(int64_t n_rows, mgg_dtype_t a_dtype, const void
     if (n_rows < 0 || d_in < 1 || d_out < 1 || ld_a < d_in || ld_out < d_out)
         return fail(MGG_ERR_INVALID_ARG, "n_rows %lld, d_in %d, d_out %d, ld_a %lld, ld_out %lld", (long long)n_rows, d_in, d_out, (long long)ld_a, (long long)ld_out);
     if (!dtype_ok(a_dtype) || !dtype_ok(w_dtype) || !dtype_ok(out_dtype)) return fail(MGG_ERR_INVALID_ARG, "unknown dtype");
-    if (act != MGG_ACT_NONE && act != MGG_ACT_RELU) return fail(MGG_ERR_INVALID_ARG, "unknown activation");
+    if (act != MGG_ACT_NONE && act != MGG_ACT_RELU && act != MGG_ACT_SOFTMAX) return fail(MGG_ERR_INVALID_ARG, "unknown activation");
     if (w_dtype == MGG_F32 && a_dtype != MGG_F32) return fail(MGG_ERR_UNSUPPORTED, "fp32 weights need fp32 input");
     if (!w || (n_rows > 0 && (!a || !out))) return fail(MGG_ERR_INVALID_ARG, "NULL matrix pointer");
     if (reinterpret_cast<uintptr_t>(a) % (a_dtype == MGG_BF16 ? 2 : 4) || reinterpret_cast<uintptr_t>(w) % (w_dtype == MGG_BF16 ? 2 : 4) ||
@@ -162,7 +162,8 @@ mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t 
         if (s == MGG_OK && n_halo > 0) s = check_update(n_halo, x_dtype, x_halo, ld_x, d0, layer->w_dtype, layer->w[0], d1, MGG_ACT_NONE, MGG_F32, t_halo, pl.ld_agg);
         if (s == MGG_OK && layer->n_linear == 2)
             s = check_update(p->n_own, MGG_F32, agg, pl.ld_agg, d1, layer->w_dtype, layer->w[1], d2, layer->act[1], out_dtype, out, ld_out);
-        if (s == MGG_OK && layer->act[0] != MGG_ACT_NONE && layer->act[0] != MGG_ACT_RELU) s = fail(MGG_ERR_INVALID_ARG, "unknown activation");
+        if (s == MGG_OK && layer->act[0] != MGG_ACT_NONE && layer->act[0] != MGG_ACT_RELU && layer->act[0] != MGG_ACT_SOFTMAX)
+            s = fail(MGG_ERR_INVALID_ARG, "unknown activation");
         if (s != MGG_OK) return s;
         if (p->n_own == 0) return MGG_OK;
         s = launch_update(p->n_own, x_dtype, x_local, ld_x, d0, layer->w_dtype, layer->w[0], nullptr, d1, MGG_ACT_NONE, MGG_F32, t_local, pl.ld_agg, st);
@@ -174,8 +175,10 @@ mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t 
         // the transformed tables are gathered at their width rounded up to whole 16-byte vectors (the
         // padding columns hold whatever the workspace held and only reach output columns that do not exist)
         const int32_t d1_padded = static_cast<int32_t>(std::min<int64_t>(round_up(static_cast<size_t>(d1), 4), pl.ld_agg));
+        const bool softmax0 = layer->act[0] == MGG_ACT_SOFTMAX;     // not an elementwise epilogue: its own pass
         s = launch_aggregate(p, layer->mode, layer->eps, MGG_F32, t_local, n_halo > 0 ? t_halo : nullptr, d1_padded, pl.ld_agg, agg,
-                             ld_aggout, st, layer->bias[0], layer->act[0], d1);
+                             ld_aggout, st, layer->bias[0], softmax0 ? MGG_ACT_NONE : layer->act[0], d1);
+        if (s == MGG_OK && softmax0) s = launch_row_softmax(p->n_own, d1, MGG_F32, agg, ld_aggout, st);
         if (s != MGG_OK || layer->n_linear == 1) return s;
         return launch_update(p->n_own, MGG_F32, agg, pl.ld_agg, d1, layer->w_dtype, layer->w[1], layer->bias[1], d2, layer->act[1],
                              out_dtype, out, ld_out, st);

@@ -106,4 +106,7 @@ mgg_status_t launch_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, i
                            mgg_act_t act, mgg_dtype_t out_dtype, void *out, int64_t ld_out,
                            hipStream_t stream);
 
+// in place: x[i][:] = softmax(x[i][:]) for every row (update.hip)
+mgg_status_t launch_row_softmax(int64_t n_rows, int32_t d, mgg_dtype_t dtype, void *x, int64_t ld, hipStream_t stream);
+
 }  // namespace mgg

@@ -399,6 +399,48 @@ void update_bf16_resident_kernel(const UpdArgs p)
 #define MGG_UPD_DEPTH_B16 1
 #endif
 
+// ---- row softmax (section 7: the last step of the 2-layer GCN) ---------------------------------
+// One wavefront per row, in place: the row is held in registers (lanes stride over the columns),
+// maximum and sum are combined with cross-lane shuffles.  Bound by HBM: one read and one write.
+template <bool BF16, int CPL>      // CPL: columns per lane
+__global__ __launch_bounds__(kThreads) void row_softmax_kernel(void *x, int64_t n_rows, int32_t d, int64_t ld)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
+    if (row >= n_rows) return;
+    float v[CPL];
+    float m = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        const int col = c * kWave + lane;
+        v[c] = -INFINITY;
+        if (col < d) {
+            if constexpr (BF16) v[c] = __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(x)[row * ld + col]) << 16);
+            else v[c] = static_cast<const float *>(x)[row * ld + col];
+        }
+        m = fmaxf(m, v[c]);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    float sum = 0.f;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        v[c] = c * kWave + lane < d ? expf(v[c] - m) : 0.f;
+        sum += v[c];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+    const float inv = 1.f / sum;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        const int col = c * kWave + lane;
+        if (col < d) {
+            if constexpr (BF16) static_cast<uint16_t *>(x)[row * ld + col] = static_cast<uint16_t>(f32_to_bf16_bits(v[c] * inv));
+            else static_cast<float *>(x)[row * ld + col] = v[c] * inv;
+        }
+    }
+}
+
 inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
 template <int NT>
@@ -421,9 +463,47 @@ hipError_t launch_shape(const UpdArgs &p, bool w_bf16, bool a_bf16, dim3 grid, h
 
 }  // namespace
 
+mgg_status_t launch_row_softmax(int64_t n_rows, int32_t d, mgg_dtype_t dtype, void *x, int64_t ld, hipStream_t stream)
+{
+    if (n_rows == 0) return MGG_OK;
+    if (d > 8 * kWave) return fail(MGG_ERR_UNSUPPORTED, "softmax over %d columns (at most %d)", d, 8 * kWave);
+    const int64_t blocks = (n_rows + kWaves - 1) / kWaves;
+    if (blocks > INT32_MAX) return fail(MGG_ERR_UNSUPPORTED, "too many rows for one launch");
+    const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+    const bool bf = dtype == MGG_BF16;
+    const int cpl = (d + kWave - 1) / kWave;
+#define MGG_SOFTMAX(C) do { if (bf) hipLaunchKernelGGL((row_softmax_kernel<true, C>), grid, block, 0, stream, x, n_rows, d, ld); \
+                            else hipLaunchKernelGGL((row_softmax_kernel<false, C>), grid, block, 0, stream, x, n_rows, d, ld); } while (0)
+    if (cpl <= 1) MGG_SOFTMAX(1);
+    else if (cpl <= 2) MGG_SOFTMAX(2);
+    else if (cpl <= 4) MGG_SOFTMAX(4);
+    else MGG_SOFTMAX(8);
+#undef MGG_SOFTMAX
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "softmax kernel launch");
+    return MGG_OK;
+}
+
+static mgg_status_t launch_update_gemm(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in,
+                                       mgg_dtype_t w_dtype, const void *w, const float *bias, int32_t d_out, mgg_act_t act,
+                                       mgg_dtype_t out_dtype, void *out, int64_t ld_out, hipStream_t stream);
+
 mgg_status_t launch_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in,
                            mgg_dtype_t w_dtype, const void *w, const float *bias, int32_t d_out, mgg_act_t act,
                            mgg_dtype_t out_dtype, void *out, int64_t ld_out, hipStream_t stream)
+{
+    // softmax couples the columns of a row: the product is written first, the rows are normalised in place
+    const bool softmax = act == MGG_ACT_SOFTMAX;
+    if (softmax && d_out > 8 * kWave) return fail(MGG_ERR_UNSUPPORTED, "softmax over %d columns (at most %d)", d_out, 8 * kWave);
+    mgg_status_t s = launch_update_gemm(n_rows, a_dtype, a, ld_a, d_in, w_dtype, w, bias, d_out, softmax ? MGG_ACT_NONE : act,
+                                        out_dtype, out, ld_out, stream);
+    if (s != MGG_OK || !softmax) return s;
+    return launch_row_softmax(n_rows, d_out, out_dtype, out, ld_out, stream);
+}
+
+static mgg_status_t launch_update_gemm(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in,
+                                       mgg_dtype_t w_dtype, const void *w, const float *bias, int32_t d_out, mgg_act_t act,
+                                       mgg_dtype_t out_dtype, void *out, int64_t ld_out, hipStream_t stream)
 {
     if (n_rows == 0) return MGG_OK;
     const bool w_bf16 = w_dtype == MGG_BF16, a_bf16 = a_dtype == MGG_BF16;

@@ -357,6 +357,29 @@ def test_update_whole_line_kernels(n_rows, d_in, d_out, w_bf16, a_bf16, out_bf16
     assert torch.equal(got[0], got[1])
 
 
+@pytest.mark.parametrize("n_rows,d_in,d_out,bf16", [(1000, 256, 47, False), (77, 64, 64, False), (513, 100, 130, False),
+                                                   (300, 128, 300, False), (5, 8, 1, False), (400, 128, 47, True)])
+def test_update_softmax(n_rows, d_in, d_out, bf16):
+    """Row softmax after the product (the last step of the 2-layer GCN of section 7).  A softmax
+    moves by at most half the change of its logits, so the bound is that of the logits plus the
+    rounding of expf and of the division."""
+    rng = np.random.default_rng(d_out)
+    a = rng.standard_normal((n_rows, d_in)).astype(np.float32)
+    w = (0.3 * rng.standard_normal((d_in, d_out))).astype(np.float32)
+    b = rng.standard_normal(d_out).astype(np.float32)
+    a_in, w_in = (inputs.to_bf16_bits(a), inputs.to_bf16_bits(w)) if bf16 else (a, w)
+    ref = oracle.update(a_in, w_in, b, "softmax")
+    s_bound = np.abs(oracle.to_f64(a_in)) @ np.abs(oracle.to_f64(w_in)) + np.abs(b)
+    logit_err = (2.0 ** -7 if bf16 else 2.0 * d_in * 2.0 ** -24) * s_bound.max(axis=1, keepdims=True)
+    buf = torch.full((n_rows, d_out + 3), float("nan"), dtype=torch.float32, device=DEV)
+    out = binding.mgg_update(to_dev(a_in), to_dev(w_in), to_dev(b), "softmax", out=buf[:, :d_out])
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:, d_out:]).all()
+    got = to_host64(out)
+    assert_close(got, ref, 1e-5, 1e-6 + logit_err, "softmax")
+    np.testing.assert_allclose(got.sum(axis=1), 1.0, rtol=1e-5)
+
+
 # ----------------------------------------------------------------------------- whole layers on the five configs
 SHRINK = {1: 0, 2: 5, 3: 7, 4: 4, 5: 6}
 
@@ -513,7 +536,8 @@ def test_update_first_order_on_the_narrowing_configs(cfg, order):
 @pytest.mark.parametrize("mode,bf16,dims,acts,with_bias", [
     ("gcn", False, (64, 47), ("relu",), True), ("gcn", False, (100, 5), ("none",), True),
     ("gin", False, (96, 32, 17), ("relu", "none"), True), ("gin", True, (128, 64, 130), ("relu", "relu"), False),
-    ("gcn", True, (136, 24), ("relu",), False), ("gcn", False, (33, 64), ("relu",), True)])
+    ("gcn", True, (136, 24), ("relu",), False), ("gcn", False, (33, 64), ("relu",), True),
+    ("gcn", False, (64, 47), ("softmax",), True), ("gin", False, (96, 32, 10), ("relu", "softmax"), True)])
 def test_update_first_matches_the_oracle(mode, bf16, dims, acts, with_bias):
     row_ptr, col, rng = small_rmat(seed=5)
     n = row_ptr.size - 1

@@ -395,3 +395,30 @@ def test_edge_balanced_split_contract(parts):
 
 def test_oracle_reports_thread_count():
     assert oracle.num_threads() >= 1
+
+
+def test_update_softmax_pins():
+    """Row softmax of the Update (section 7: Z = softmax(A-hat ReLU(A-hat X W0) W1)): the plain
+    definition exp(z_j) / sum_k exp(z_k) evaluated directly, the library routine, the two-class
+    closed form, and the properties a dropped normalisation, a column-wise instead of row-wise sum or
+    a missing bias would break."""
+    import scipy.special
+    rng = np.random.default_rng(21)
+    a = rng.standard_normal((37, 9))
+    w = rng.standard_normal((9, 5))
+    b = rng.standard_normal(5)
+    z = a @ w + b
+    got = oracle.update(a, w, b, "softmax")
+    plain = np.exp(z) / np.exp(z).sum(axis=1, keepdims=True)
+    np.testing.assert_allclose(got, plain, rtol=1e-13, atol=0)
+    np.testing.assert_allclose(got, scipy.special.softmax(z, axis=1), rtol=1e-13, atol=0)
+    np.testing.assert_allclose(got.sum(axis=1), 1.0, rtol=1e-14)
+    assert np.all(got > 0) and np.array_equal(np.argmax(got, axis=1), np.argmax(z, axis=1))
+    # adding a constant to every logit of a row changes nothing; logits of 800 do not overflow
+    np.testing.assert_allclose(oracle.update(a, w, b + 800.0, "softmax"), got, rtol=1e-10)
+    # two classes: softmax(z)_0 = 1 / (1 + exp(z_1 - z_0))
+    z2 = oracle.update(a, w[:, :2], b[:2], "none")
+    np.testing.assert_allclose(oracle.update(a, w[:, :2], b[:2], "softmax")[:, 0], 1.0 / (1.0 + np.exp(z2[:, 1] - z2[:, 0])), rtol=1e-13)
+    # hand value: softmax([0, ln 2, ln 5]) = [1, 2, 5] / 8
+    np.testing.assert_allclose(oracle.update(np.array([[1.0]]), np.array([[0.0, np.log(2.0), np.log(5.0)]]), None, "softmax"),
+                               [[0.125, 0.25, 0.625]], rtol=1e-15)
