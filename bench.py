@@ -289,6 +289,56 @@ def run_orders(cfg: int, iters: int = 20):
     return {"workload": w.name, "edges": nnz, "n_own": int(info.n_own), "num_halo": int(info.num_halo), "layers": rows}
 
 
+UPDATE_SHAPES = [
+    # name, rows, d_in, d_out, dtype of A, dtype of W, dtype of out -- the Update calls of the five configs
+    ("cfg2 64->64", 262144, 64, 64, "f32", "f32", "f32"),
+    ("cfg3 128->128 (linear 1)", 524288, 128, 128, "f32", "bf16", "bf16"),
+    ("cfg3 128->128 (linear 2)", 524288, 128, 128, "bf16", "bf16", "f32"),
+    ("cfg4 602->256", 232965, 602, 256, "f32", "f32", "f32"),
+    ("cfg5 100->256", 306128, 100, 256, "f32", "f32", "f32"),
+    ("cfg5 256->47", 306128, 256, 47, "f32", "f32", "f32"),
+    ("cfg5 256->47, halo rows", 1771062, 256, 47, "f32", "f32", "f32"),
+]
+
+
+def run_update_shapes(iters: int = 20, vendor: bool = True):
+    """mgg_update alone on the Update shapes of the configs (ReLU fused), HIP events on the launch
+    stream; torch.matmul -- the vendor GEMM, no epilogue, one dtype for input and output -- beside it."""
+    import torch
+    from paper_2209_06800_amd import binding
+    dev = "cuda:0"
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16}
+    rows = []
+    for name, n, k, m, adt, wdt, odt in UPDATE_SHAPES:
+        a = torch.randn(n, k, device=dev).to(tdt[adt])
+        w = (torch.randn(k, m, device=dev) * 0.1).to(tdt[wdt])
+        out = torch.empty(n, m, device=dev, dtype=tdt[odt])
+
+        def timed(fn):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / iters
+
+        ms = timed(lambda: binding.mgg_update(a, w, None, "relu", out=out))
+        byts = n * k * a.element_size() + n * m * out.element_size() + k * m * w.element_size()
+        r = {"shape": name, "rows": n, "d_in": k, "d_out": m, "dtypes": f"{adt}/{wdt}/{odt}", "us": round(ms * 1e3, 1),
+             "tflops": round(2.0 * n * k * m / ms / 1e9, 1), "gbs": round(byts / ms / 1e6)}
+        if vendor:
+            av, wv = a.to(tdt[wdt]), w
+            ov = torch.empty(n, m, device=dev, dtype=tdt[wdt])
+            r["vendor_us"] = round(timed(lambda: torch.matmul(av, wv, out=ov)) * 1e3, 1)
+        rows.append(r)
+        log(f"[update] {name}: {r['us']} us, {r['tflops']} TFLOP/s, {r['gbs']} GB/s" + (f" (vendor GEMM {r['vendor_us']} us)" if vendor else ""))
+        del a, w, out
+    return rows
+
+
 def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 20.0, calibrate_copy: bool = False):
     import torch
     from paper_2209_06800_amd import binding, inputs
@@ -448,6 +498,9 @@ def main():
                     help="run the greedy search over ps / dist / wpb (section 6) on layer 0's aggregation and exit")
     ap.add_argument("--tune-exhaustive", action="store_true",
                     help="like --tune, and measure the whole 150-point grid beside it")
+    ap.add_argument("--update-shapes", action="store_true",
+                    help="time mgg_update alone on the Update shapes of the five configs and exit")
+    ap.add_argument("--no-vendor", action="store_true", help="with --update-shapes: skip the torch.matmul comparison")
     ap.add_argument("--compare-orders", action="store_true",
                     help="time every layer as Update(Aggregate(X)) and as Aggregate(X W) (+ bias, activation) and exit")
     ap.add_argument("--calibrate-gather", action="store_true",
@@ -460,6 +513,9 @@ def main():
         print("bench.py measures one GPU's share on one MI355X; multi-GPU runs are not part of this build "
               "(no collectives, no second GPU). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    if args.update_shapes:
+        print(json.dumps({"update_shapes": run_update_shapes(vendor=not args.no_vendor)}), flush=True)
+        return
     if args.compare_orders:
         print(json.dumps(run_orders(args.config)), flush=True)
         return

@@ -83,6 +83,81 @@ __global__ __launch_bounds__(kThreads) void update_f32_kernel(const UpdArgs p)
     store_tiles<NT>(p, acc, m0, n0, lane);
 }
 
+// The same tile with two W slabs in LDS: the next slab travels from global memory into registers
+// while the current one is multiplied and is written to the other buffer afterwards, so a K slab
+// costs one barrier and the load latency of W is off the critical path.  For weight matrices whose
+// rows allow 16-byte loads and whose width is a whole number of workgroup tiles.
+extern __shared__ __attribute__((aligned(16))) unsigned char w_db[];
+
+template <int NT, int WN>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void update_f32_db_kernel(const UpdArgs p)
+{
+    constexpr int BK = 32, NC = NT * 32 * WN, WM = kWaves / WN;
+    constexpr int UNITS = BK * NC / 4 / kThreads;          // 16-byte pieces of a W slab per thread
+    float *w_lds = reinterpret_cast<float *>(w_db);         // [2][BK * NC]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 31, h = lane >> 5;
+    const int wm = wave / WN, wn = wave % WN;
+    const int64_t m0 = (static_cast<int64_t>(blockIdx.x) * WM + wm) * 32;
+    const int nb = blockIdx.y * NC;
+    const int n0 = nb + wn * NT * 32;
+    const float *W = static_cast<const float *>(p.w);
+    const int64_t row = m0 + i < p.n_rows ? m0 + i : p.n_rows - 1;
+    const float *arow = static_cast<const float *>(p.a) + row * p.ld_a;
+
+    float4 wreg[UNITS];
+    auto load_w = [&](int k_begin) {
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            const int id = u * kThreads + threadIdx.x, kk = id / (NC / 4), n4 = id % (NC / 4);
+            wreg[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k_begin + kk < p.d_in) wreg[u] = *reinterpret_cast<const float4 *>(W + static_cast<int64_t>(k_begin + kk) * p.d_out + nb + 4 * n4);
+        }
+    };
+    auto store_w = [&](float *buf) {
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) reinterpret_cast<float4 *>(buf)[u * kThreads + threadIdx.x] = wreg[u];
+    };
+
+    f32x16 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+    float af[16], an[16];
+    load_w(0);
+    load_a_f32(p, arow, 16 * h, BK, af);
+    store_w(w_lds);
+    __syncthreads();
+    int cur = 0;
+#pragma unroll 1
+    for (int k0 = 0; k0 < p.d_in; k0 += BK) {
+        const bool more = k0 + BK < p.d_in;                  // uniform over the workgroup
+        if (more) {
+            load_w(k0 + BK);
+            load_a_f32(p, arow, k0 + BK + 16 * h, k0 + 2 * BK, an);
+        }
+        const float *wbuf = w_lds + cur * (BK * NC);
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const float *wrow = wbuf + (16 * h + c) * NC + wn * NT * 32 + i;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(wrow[t * 32], af[c], acc[t], 0, 0, 0);
+        }
+        if (more) {
+            store_w(w_lds + (cur ^ 1) * (BK * NC));
+#pragma unroll
+            for (int c = 0; c < 16; ++c) af[c] = an[c];
+        }
+        __syncthreads();
+        cur ^= 1;
+    }
+    store_tiles<NT>(p, acc, m0, n0, lane);
+}
+
 // ---- bf16 weights: v_mfma_f32_32x32x16_bf16 -------------------------------------------------
 // K slab of 64: lane (i, h) holds A[m0+i][k0 + 32h .. k0 + 32h + 31] as four 8-element
 // operands; MFMA number c contracts k0 + 32h + 8c .. + 7 (both halves h at once).
@@ -455,7 +530,16 @@ hipError_t launch_resident(const UpdArgs &p, bool w_bf16, bool a_bf16, int block
 template <int NT, int WN>
 hipError_t launch_shape(const UpdArgs &p, bool w_bf16, bool a_bf16, dim3 grid, hipStream_t s)
 {
-    if (!w_bf16) hipLaunchKernelGGL((update_f32_kernel<NT, WN>), grid, dim3(kThreads), 0, s, p);
+    if (!w_bf16 && p.w_vec_ok && p.d_out % (NT * 32 * WN) == 0 && option_update_stream() != 0) {
+        constexpr int lds_bytes = 2 * 32 * NT * 32 * WN * 4;
+        static bool raised = false;     // more than 64 KB of dynamic LDS has to be asked for once
+        if (lds_bytes > 48 * 1024 && !raised) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&update_f32_db_kernel<NT, WN>), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            raised = true;
+        }
+        hipLaunchKernelGGL((update_f32_db_kernel<NT, WN>), grid, dim3(kThreads), lds_bytes, s, p);
+    }
+    else if (!w_bf16) hipLaunchKernelGGL((update_f32_kernel<NT, WN>), grid, dim3(kThreads), 0, s, p);
     else if (a_bf16) hipLaunchKernelGGL((update_bf16_kernel<NT, WN, true>), grid, dim3(kThreads), 0, s, p);
     else hipLaunchKernelGGL((update_bf16_kernel<NT, WN, false>), grid, dim3(kThreads), 0, s, p);
     return hipGetLastError();
