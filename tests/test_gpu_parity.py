@@ -1,6 +1,6 @@
 """Parity of the HIP path with the CPU oracle, element by element, through the C ABI.
 
-Tolerances (written out here, derived in the design doc):
+Tolerances (written out here; each follows from the forward-error bound of an fp32 or bf16 sum):
   fp32 aggregation, GCN ... |gpu - ref| <= 1e-6 + 1e-4 |ref|
   fp32 aggregation, GIN ... |gpu - ref| <= 1e-6 max(1, sum|x_u|) + 1e-4 |ref|   (unnormalised sums:
                             the absolute term has to follow the magnitude of what is added up)
