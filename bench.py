@@ -90,8 +90,14 @@ def cpu_baseline_leg(w, layer, x_local_np, x_halo_np, halo_gid, n_own, cpu_budge
     for i, m in enumerate(layer.weights):
         h = oracle.update(h, m, None, layer.acts[i])
     cpu_s = time.perf_counter() - t0
+    cpu_model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            cpu_model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), cpu_model)
+    except OSError:
+        pass
     return {"value": round(sample_edges / cpu_s / 1e9, 5), "unit": "GEdges/s", "cores": oracle.num_threads(),
-            "kind": "oracle",
+            "kind": "oracle", "cpu": cpu_model,
             "sample": f"layer 0 (aggregate + update) on {rows.size} of {n_own} owned rows, "
                       f"{sample_edges} edges, {cpu_s:.1f}s"}
 
@@ -341,7 +347,8 @@ def run_update_shapes(iters: int = 20, vendor: bool = True):
     return rows
 
 
-def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 20.0, calibrate_copy: bool = False):
+def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 20.0, calibrate_copy: bool = False,
+        cold_iters: int = 5, part_id=None):
     import torch
     from paper_2209_06800_amd import binding, inputs
 
@@ -349,6 +356,12 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
     torch.cuda.set_device(0)
     t0 = time.time()
     w = inputs.config(cfg)
+    if part_id is not None and part_id != w.part_id:
+        # another share of the same graph (share 0, the heaviest under the equal-node split, is the default)
+        if not 0 <= part_id < w.parts:
+            raise SystemExit(f"--part-id must be in [0, {w.parts})")
+        w.part_id = part_id
+        w.name += f"_share{part_id}"
     log(f"[bench] generated {w.name}: {inputs.graph_stats(w.row_ptr)} in {time.time() - t0:.1f}s")
     t0 = time.time()
     part = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
@@ -427,8 +440,28 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
     elapsed = time.perf_counter() - t_start
     ms_per_step = elapsed * 1e3 / steps
 
-    agg_ms = [float(np.mean([ev[k][li][0].elapsed_time(ev[k][li][1]) for k in range(steps)])) for li in range(len(layers))]
-    upd_ms = [float(np.mean([ev[k][li][1].elapsed_time(ev[k][li][2]) for k in range(steps)])) for li in range(len(layers))]
+    agg_all = [[ev[k][li][0].elapsed_time(ev[k][li][1]) for k in range(steps)] for li in range(len(layers))]
+    upd_all = [[ev[k][li][1].elapsed_time(ev[k][li][2]) for k in range(steps)] for li in range(len(layers))]
+    agg_ms = [float(np.mean(v)) for v in agg_all]
+    upd_ms = [float(np.mean(v)) for v in upd_all]
+
+    # Outside the timed region: the same aggregations with cold caches.  Between two launches a 1 GiB
+    # scratch buffer is overwritten, which pushes the tables out of L2 and of the Infinity Cache.
+    cold_ms = [None] * len(layers)
+    if cold_iters > 0:
+        scratch = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        cold = [[] for _ in layers]
+        for _ in range(cold_iters):
+            for li, L in enumerate(layers):
+                scratch.fill_(1.0)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                binding.mgg_aggregate(part, L["layer"].mode, L["xl"], L["xh"], eps=L["layer"].eps, out=L["agg"])
+                e1.record()
+                torch.cuda.synchronize()
+                cold[li].append(e0.elapsed_time(e1))
+        cold_ms = [float(np.median(v)) for v in cold]
+        del scratch
     dom = int(np.argmax([L["bytes"] for L in layers]))
     achieved = layers[dom]["bytes"] / (agg_ms[dom] * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
@@ -440,6 +473,8 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
             "agg_gedges_per_s": round(nnz / (agg_ms[li] * 1e-3) / 1e9, 3),
             "agg_model_gbs": round(L["bytes"] / (agg_ms[li] * 1e-3) / 1e9, 1),
             "agg_frac_of_hbm_peak": round(L["bytes"] / (agg_ms[li] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "agg_ms_median": round(float(np.median(agg_all[li])), 4), "agg_ms_min": round(float(np.min(agg_all[li])), 4),
+            "agg_ms_cold_cache": None if cold_ms[li] is None else round(cold_ms[li], 4),
             "update_ms": round(upd_ms[li], 4),
             "update_tflops": round(L["flops"] / (upd_ms[li] * 1e-3) / 1e12, 2),
         })
@@ -500,6 +535,9 @@ def main():
                     help="run the greedy search over ps / dist / wpb (section 6) on layer 0's aggregation and exit")
     ap.add_argument("--tune-exhaustive", action="store_true",
                     help="like --tune, and measure the whole 150-point grid beside it")
+    ap.add_argument("--cold-iters", type=int, default=5,
+                    help="aggregation launches per layer timed with cold caches after the timed region (0 = skip)")
+    ap.add_argument("--part-id", type=int, default=None, help="time another share of the graph than share 0")
     ap.add_argument("--update-shapes", action="store_true",
                     help="time mgg_update alone on the Update shapes of the five configs and exit")
     ap.add_argument("--no-vendor", action="store_true", help="with --update-shapes: skip the torch.matmul comparison")
@@ -530,7 +568,8 @@ def main():
     if args.ablations:
         print(json.dumps({"workload_config": args.config, "ablations": run_ablations(args.config)}), flush=True)
         return
-    res = run(args.config, args.steps, args.warmup, args.verify, args.cpu_seconds, args.calibrate_copy)
+    res = run(args.config, args.steps, args.warmup, args.verify, args.cpu_seconds, args.calibrate_copy,
+              args.cold_iters, args.part_id)
     print(json.dumps(res), flush=True)
 
 
