@@ -348,7 +348,7 @@ def run_update_shapes(iters: int = 20, vendor: bool = True):
 
 
 def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 20.0, calibrate_copy: bool = False,
-        cold_iters: int = 5, part_id=None):
+        cold_iters: int = 5, part_id=None, split: str = "nodes"):
     import torch
     from paper_2209_06800_amd import binding, inputs
 
@@ -356,6 +356,11 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
     torch.cuda.set_device(0)
     t0 = time.time()
     w = inputs.config(cfg)
+    if split == "edges" and w.parts > 1:
+        # Algorithm 1 (section 4.1 Step-1): contiguous ranges with about E / P edges each instead of N / P nodes
+        from paper_2209_06800_amd import binding as _b
+        w.bounds = _b.mgg_split_edge_balanced(w.row_ptr, w.parts)
+        w.name += "_edge_balanced"
     if part_id is not None and part_id != w.part_id:
         # another share of the same graph (share 0, the heaviest under the equal-node split, is the default)
         if not 0 <= part_id < w.parts:
@@ -537,6 +542,8 @@ def main():
                     help="like --tune, and measure the whole 150-point grid beside it")
     ap.add_argument("--cold-iters", type=int, default=5,
                     help="aggregation launches per layer timed with cold caches after the timed region (0 = skip)")
+    ap.add_argument("--split", choices=["nodes", "edges"], default="nodes",
+                    help="node ranges of the shares: equal node counts (default) or the edge-balanced split of Algorithm 1")
     ap.add_argument("--part-id", type=int, default=None, help="time another share of the graph than share 0")
     ap.add_argument("--update-shapes", action="store_true",
                     help="time mgg_update alone on the Update shapes of the five configs and exit")
@@ -569,7 +576,7 @@ def main():
         print(json.dumps({"workload_config": args.config, "ablations": run_ablations(args.config)}), flush=True)
         return
     res = run(args.config, args.steps, args.warmup, args.verify, args.cpu_seconds, args.calibrate_copy,
-              args.cold_iters, args.part_id)
+              args.cold_iters, args.part_id, args.split)
     print(json.dumps(res), flush=True)
 
 
