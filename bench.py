@@ -344,6 +344,24 @@ def run_update_shapes(iters: int = 20, vendor: bool = True):
         rows.append(r)
         log(f"[update] {name}: {r['us']} us, {r['tflops']} TFLOP/s, {r['gbs']} GB/s" + (f" (vendor GEMM {r['vendor_us']} us)" if vendor else ""))
         del a, w, out
+    # config 3's MLP as one call: both products in one kernel, hidden activations kept on chip
+    n, k = 524288, 128
+    a = torch.randn(n, k, device=dev)
+    w1, w2 = [(torch.randn(k, k, device=dev) * 0.1).bfloat16() for _ in range(2)]
+    out = torch.empty(n, k, device=dev)
+    for _ in range(3):
+        binding.mgg_update_mlp(a, w1, w2, ("relu", "none"), out=out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        binding.mgg_update_mlp(a, w1, w2, ("relu", "none"), out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    r = {"shape": "cfg3 MLP 128->128->128, one kernel", "rows": n, "d_in": k, "d_out": k, "dtypes": "f32/bf16/f32", "us": round(ms * 1e3, 1),
+         "tflops": round(4.0 * n * k * k / ms / 1e9, 1), "gbs": round((n * k * 8 + 4 * k * k) / ms / 1e6), "vendor_us": None}
+    rows.append(r)
+    log(f"[update] {r['shape']}: {r['us']} us, {r['tflops']} TFLOP/s, {r['gbs']} GB/s")
     return rows
 
 
@@ -417,8 +435,7 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
             if len(L["ws"]) == 1:
                 binding.mgg_update(L["agg"], L["ws"][0], None, layer.acts[0], out=L["out"])
             else:
-                binding.mgg_update(L["agg"], L["ws"][0], None, layer.acts[0], out=L["hid"])
-                binding.mgg_update(L["hid"], L["ws"][1], None, layer.acts[1], out=L["out"])
+                binding.mgg_update_mlp(L["agg"], L["ws"][0], L["ws"][1], layer.acts, hidden=L["hid"], out=L["out"])
             if events is not None:
                 events[li][2].record()
 

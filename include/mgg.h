@@ -184,6 +184,21 @@ mgg_status_t mgg_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int6
                         mgg_dtype_t w_dtype, const void *w, const float *bias, int32_t d_out,
                         mgg_act_t act, mgg_dtype_t out_dtype, void *out, int64_t ld_out, void *stream);
 
+/* ---------------------------------------------------------------------------------------
+ * mgg_update_mlp -- section 7, GIN: the Update is an MLP; two chained mgg_update calls,
+ *     out = act2(act1(a . w1 + bias1) . w2 + bias2),      dims = {d_in, d_hidden, d_out}.
+ * With bf16 weights, fp32 a, d_in 64 or 128, 33..128 hidden and output columns and
+ * elementwise activations both products run in ONE kernel and the hidden activations stay
+ * in registers (rounded to bf16, as the two-call form keeps them).  Any other shape runs as
+ * two launches through `hidden`, a DEVICE buffer [n_rows x d_hidden] (bf16 with bf16
+ * weights, fp32 otherwise), which may be NULL only when the one-kernel form applies
+ * (else MGG_ERR_INVALID_ARG).  Other arguments and errors as in mgg_update.
+ * ------------------------------------------------------------------------------------- */
+mgg_status_t mgg_update_mlp(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, const int32_t *dims,
+                            mgg_dtype_t w_dtype, const void *w1, const float *bias1, mgg_act_t act1,
+                            const void *w2, const float *bias2, mgg_act_t act2,
+                            void *hidden, int64_t ld_hidden, mgg_dtype_t out_dtype, void *out, int64_t ld_out, void *stream);
+
 /* Order of the aggregation and of the first linear of the Update.  Aggregation is linear, so
  * Aggregate(X) W = Aggregate(X W) (section 7: A-hat X W is one product); when W narrows the rows
  * the second form gathers d_out-wide rows instead of d_in-wide ones.  Values agree within

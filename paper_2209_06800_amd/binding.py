@@ -27,7 +27,7 @@ _STATUS_NAME = ["OK", "INVALID_ARG", "BAD_GRAPH", "UNSUPPORTED", "ALLOC", "HIP"]
 
 EXPORTED_SYMBOLS = [
     "mgg_build_partition", "mgg_partition_info", "mgg_partition_export", "mgg_partition_destroy",
-    "mgg_aggregate", "mgg_update", "mgg_layer_workspace_bytes", "mgg_layer_forward",
+    "mgg_aggregate", "mgg_update", "mgg_update_mlp", "mgg_layer_workspace_bytes", "mgg_layer_forward",
     "mgg_split_edge_balanced", "mgg_set_option", "mgg_get_option", "mgg_time_aggregate",
     "mgg_model_evaluate", "mgg_tuner_create", "mgg_tuner_next", "mgg_tuner_report", "mgg_tuner_result",
     "mgg_tuner_table", "mgg_tuner_destroy", "mgg_tune_aggregate",
@@ -113,6 +113,9 @@ def lib():
                                     C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
         L.mgg_update.argtypes = [C.c_int64, C.c_int, C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p,
                                  C.c_void_p, C.c_int32, C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
+        L.mgg_update_mlp.argtypes = [C.c_int64, C.c_int, C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_int, C.c_void_p,
+                                     C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int64, C.c_int,
+                                     C.c_void_p, C.c_int64, C.c_void_p]
         L.mgg_layer_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(LayerDesc)]
         L.mgg_layer_forward.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.c_int, C.c_void_p, C.c_void_p,
                                         C.c_int64, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_int64,
@@ -304,6 +307,23 @@ def mgg_update(a, w, bias=None, act: str = "none", *, out=None, out_dtype=None, 
     _check(lib().mgg_update(n_rows, _torch_dtype_code(a), _dev_ptr(a), _ld(a), d_in, _torch_dtype_code(w),
                             _dev_ptr(w), _dev_ptr(bias), d_out, _ACT[act], _torch_dtype_code(out), _dev_ptr(out),
                             _ld(out), _stream(stream)))
+    return out
+
+
+def mgg_update_mlp(a, w1, w2, acts=("relu", "none"), biases=(None, None), *, hidden=None, out=None, out_dtype=None,
+                   stream=None):
+    """out = act2(act1(a @ w1 + b1) @ w2 + b2); one kernel when the shape allows, else two through `hidden`."""
+    import torch
+    n_rows = int(a.shape[0])
+    dims = (C.c_int32 * 3)(int(w1.shape[0]), int(w1.shape[1]), int(w2.shape[1]))
+    if int(a.shape[1]) != dims[0] or int(w2.shape[0]) != dims[1] or not (w1.is_contiguous() and w2.is_contiguous()):
+        raise ValueError("contiguous [d_in x d_hid] and [d_hid x d_out] matrices expected")
+    if out is None:
+        out = torch.empty((n_rows, dims[2]), dtype=out_dtype or torch.float32, device=a.device)
+    _check(lib().mgg_update_mlp(n_rows, _torch_dtype_code(a), _dev_ptr(a), _ld(a), dims, _torch_dtype_code(w1), _dev_ptr(w1),
+                                _dev_ptr(biases[0]), _ACT[acts[0]], _dev_ptr(w2), _dev_ptr(biases[1]), _ACT[acts[1]],
+                                _dev_ptr(hidden), 0 if hidden is None else _ld(hidden), _torch_dtype_code(out), _dev_ptr(out),
+                                _ld(out), _stream(stream)))
     return out
 
 

@@ -204,11 +204,26 @@ mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t 
     if (layer->n_linear == 1)
         return launch_update(p->n_own, MGG_F32, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], layer->bias[0], d1,
                              layer->act[0], out_dtype, out, ld_out, st);
-    s = launch_update(p->n_own, MGG_F32, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], layer->bias[0], d1, layer->act[0],
-                      pl.hid_dtype, hid, pl.ld_hid, st);
+    return launch_update_mlp(p->n_own, MGG_F32, agg, pl.ld_agg, layer->dims, layer->w_dtype, layer->w[0], layer->bias[0], layer->act[0],
+                             layer->w[1], layer->bias[1], layer->act[1], hid, pl.ld_hid, out_dtype, out, ld_out, st);
+}
+
+mgg_status_t mgg_update_mlp(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, const int32_t *dims, mgg_dtype_t w_dtype,
+                            const void *w1, const float *bias1, mgg_act_t act1, const void *w2, const float *bias2, mgg_act_t act2,
+                            void *hidden, int64_t ld_hidden, mgg_dtype_t out_dtype, void *out, int64_t ld_out, void *stream)
+{
+    if (!dims) return fail(MGG_ERR_INVALID_ARG, "dims is NULL");
+    const mgg_dtype_t hid_dtype = w_dtype == MGG_BF16 ? MGG_BF16 : MGG_F32;
+    // Both products are checked as if they ran one after the other.  `hidden` may be NULL (the one-kernel
+    // form needs none; launch_update_mlp refuses NULL when it has to fall back): `out` then stands in for it
+    // in the checks, which only look at NULL-ness and alignment.
+    const void *hid_probe = hidden ? hidden : out;
+    const int64_t ld_probe = hidden ? ld_hidden : dims[1];
+    mgg_status_t s = check_update(n_rows, a_dtype, a, ld_a, dims[0], w_dtype, w1, dims[1], act1, hid_dtype, hid_probe, ld_probe);
+    if (s == MGG_OK) s = check_update(n_rows, hid_dtype, hid_probe, ld_probe, dims[1], w_dtype, w2, dims[2], act2, out_dtype, out, ld_out);
     if (s != MGG_OK) return s;
-    return launch_update(p->n_own, pl.hid_dtype, hid, pl.ld_hid, d1, layer->w_dtype, layer->w[1], layer->bias[1], d2,
-                         layer->act[1], out_dtype, out, ld_out, st);
+    return launch_update_mlp(n_rows, a_dtype, a, ld_a, dims, w_dtype, w1, bias1, act1, w2, bias2, act2, hidden, ld_hidden, out_dtype, out,
+                             ld_out, static_cast<hipStream_t>(stream));
 }
 
 mgg_status_t mgg_set_option(const char *key, int32_t value)

@@ -106,6 +106,12 @@ mgg_status_t launch_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, i
                            mgg_act_t act, mgg_dtype_t out_dtype, void *out, int64_t ld_out,
                            hipStream_t stream);
 
+// Two chained Updates; one kernel when the shape is covered, otherwise two launches through `hidden`
+// ([n_rows x dims[1]], bf16 with bf16 weights, else fp32).
+mgg_status_t launch_update_mlp(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, const int32_t dims[3],
+                               mgg_dtype_t w_dtype, const void *w1, const float *b1, mgg_act_t act1, const void *w2, const float *b2,
+                               mgg_act_t act2, void *hidden, int64_t ld_hidden, mgg_dtype_t out_dtype, void *out, int64_t ld_out,
+                               hipStream_t stream);
 // in place: x[i][:] = softmax(x[i][:]) for every row (update.hip)
 mgg_status_t launch_row_softmax(int64_t n_rows, int32_t d, mgg_dtype_t dtype, void *x, int64_t ld, hipStream_t stream);
 

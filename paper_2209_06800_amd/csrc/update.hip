@@ -585,6 +585,29 @@ mgg_status_t launch_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, i
     return launch_row_softmax(n_rows, d_out, out_dtype, out, ld_out, stream);
 }
 
+mgg_status_t launch_update_mlp(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, const int32_t dims[3],
+                               mgg_dtype_t w_dtype, const void *w1, const float *b1, mgg_act_t act1, const void *w2, const float *b2,
+                               mgg_act_t act2, void *hidden, int64_t ld_hidden, mgg_dtype_t out_dtype, void *out, int64_t ld_out,
+                               hipStream_t stream)
+{
+    if (n_rows == 0) return MGG_OK;
+    if (w_dtype == MGG_BF16 && a_dtype == MGG_F32 && option_update_stream() != 0) {
+        int dev = 0, cus = 256;
+        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        hipError_t e = hipSuccess;
+        if (launch_mlp_stream(n_rows, static_cast<const float *>(a), ld_a, dims[0], w1, b1, act1, dims[1], w2, b2, act2, dims[2], out_dtype,
+                              out, ld_out, cus, stream, &e)) {
+            if (e != hipSuccess) return hip_fail(e, "MLP kernel launch");
+            return MGG_OK;
+        }
+    }
+    if (!hidden) return fail(MGG_ERR_INVALID_ARG, "hidden buffer is NULL and the shape is not covered by the one-kernel MLP");
+    const mgg_dtype_t hid_dtype = w_dtype == MGG_BF16 ? MGG_BF16 : MGG_F32;
+    mgg_status_t s = launch_update(n_rows, a_dtype, a, ld_a, dims[0], w_dtype, w1, b1, dims[1], act1, hid_dtype, hidden, ld_hidden, stream);
+    if (s != MGG_OK) return s;
+    return launch_update(n_rows, hid_dtype, hidden, ld_hidden, dims[1], w_dtype, w2, b2, dims[2], act2, out_dtype, out, ld_out, stream);
+}
+
 static mgg_status_t launch_update_gemm(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in,
                                        mgg_dtype_t w_dtype, const void *w, const float *bias, int32_t d_out, mgg_act_t act,
                                        mgg_dtype_t out_dtype, void *out, int64_t ld_out, hipStream_t stream)

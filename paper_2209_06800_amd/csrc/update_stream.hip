@@ -319,6 +319,155 @@ void update_f32_stream_kernel(const UpdArgs p)
     while (tile < n_tiles) do_tile();
 }
 
+// ---- two linears in one kernel (GIN's MLP, section 7) ------------------------------------------
+// out = act2(act1(A W1 + b1) W2 + b2) with bf16 weights, fp32 A (the aggregation result), a hidden
+// width of at most 128.  The hidden tile never leaves the registers: the accumulators of the first
+// product (register r of lane (m, h), tile t: row m, hidden column 32 t + 8 (r/4) + 4 h + r%4) get bias
+// and ReLU, are rounded to bf16 -- as the hidden activations of the two-launch path are -- and eight
+// consecutive registers packed together are, as they stand, the A operand of one MFMA of the second
+// product.  MFMA sums over k in any order, so W2 is staged in LDS with its k index permuted to
+// match: within every group of 16, hidden column 8 a + 4 h + e sits at position 8 h + 4 a + e.
+constexpr int kMlpWaves = 8;
+constexpr int kMlpThreads = kWave * kMlpWaves;
+
+struct MlpArgs {
+    const float *a;
+    const uint16_t *w1, *w2;
+    const float *b1, *b2;
+    void *out;
+    int64_t n_rows, ld_a, ld_out;
+    int32_t d_in, d_hid, d_out;
+    int32_t relu1, relu2, out_vec_ok;
+};
+
+template <int NS1, int NT2, bool OUT_BF16>
+__global__ __launch_bounds__(kMlpThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void mlp_bf16_stream_kernel(const MlpArgs m)
+{
+    constexpr int BK = 64, NT1 = 4, H = NT1 * 32, LDA = BK + 8, LDW1 = NS1 * BK + 8, LDW2 = H + 8, NC2 = NT2 * 32;
+    constexpr int W1_BYTES = (H * LDW1 * 2 + 15) / 16 * 16, W2_BYTES = (NC2 * LDW2 * 2 + 15) / 16 * 16;
+    constexpr int WAVE_BYTES = wave_lds_bytes<NT2, OUT_BF16>(32 * LDA * 2);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 31, h = lane >> 5;
+    uint16_t *w1_lds = reinterpret_cast<uint16_t *>(lds_all);
+    uint16_t *w2_lds = reinterpret_cast<uint16_t *>(lds_all + W1_BYTES);
+    uint16_t *abuf = reinterpret_cast<uint16_t *>(lds_all + W1_BYTES + W2_BYTES + wave * WAVE_BYTES);
+    {
+        // W1^T [H][LDW1] and W2^T [NC2][LDW2] (k permuted), zero outside the matrices; pairs of k per dword
+        uint32_t *l1 = reinterpret_cast<uint32_t *>(w1_lds), *l2 = reinterpret_cast<uint32_t *>(w2_lds);
+        for (int id = threadIdx.x; id < (NS1 * BK / 2) * H; id += kMlpThreads) {
+            const int k = 2 * (id / H), n = id % H;
+            const uint32_t lo = (k < m.d_in && n < m.d_hid) ? m.w1[static_cast<int64_t>(k) * m.d_hid + n] : 0u;
+            const uint32_t hi = (k + 1 < m.d_in && n < m.d_hid) ? m.w1[static_cast<int64_t>(k + 1) * m.d_hid + n] : 0u;
+            l1[n * (LDW1 / 2) + k / 2] = lo | (hi << 16);
+        }
+        for (int id = threadIdx.x; id < (H / 2) * NC2; id += kMlpThreads) {
+            const int k = 2 * (id / NC2), n = id % NC2;
+            const uint32_t lo = (k < m.d_hid && n < m.d_out) ? m.w2[static_cast<int64_t>(k) * m.d_out + n] : 0u;
+            const uint32_t hi = (k + 1 < m.d_hid && n < m.d_out) ? m.w2[static_cast<int64_t>(k + 1) * m.d_out + n] : 0u;
+            const int o = k & 15, kp = (k & ~15) + 8 * ((o >> 2) & 1) + 4 * (o >> 3) + (o & 3);
+            l2[n * (LDW2 / 2) + kp / 2] = lo | (hi << 16);
+        }
+    }
+    __syncthreads();
+
+    UpdArgs pa{};           // what the slab loads and the epilogue read
+    pa.a = m.a; pa.n_rows = m.n_rows; pa.ld_a = m.ld_a;
+    pa.out = m.out; pa.ld_out = m.ld_out; pa.d_out = m.d_out; pa.bias = m.b2; pa.relu = m.relu2; pa.out_vec_ok = m.out_vec_ok;
+
+    const int64_t n_tiles = (m.n_rows + 31) / 32, stride = static_cast<int64_t>(gridDim.x) * kMlpWaves;
+    int64_t tile = static_cast<int64_t>(blockIdx.x) * kMlpWaves + wave;
+    if (tile >= n_tiles) return;
+    int64_t itile = tile;
+    int is = 0;
+    Raw<false> q;
+    auto issue = [&]() {
+        Raw<false> r;
+        load_slab<false>(pa, itile, is, lane, r);
+        if (++is == NS1) { is = 0; itile += stride; }
+        return r;
+    };
+    q = issue();
+
+    auto do_tile = [&]() {
+        f32x16 acc[NT1];
+#pragma unroll
+        for (int t = 0; t < NT1; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < NS1; ++s) {
+            stage_slab<false, LDA>(q, abuf, lane);
+            q = issue();
+            wave_sync_lds();
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                Frag8 af;
+                af.q = *reinterpret_cast<const uint4 *>(abuf + i * LDA + 32 * h + 8 * c);
+#pragma unroll
+                for (int t = 0; t < NT1; ++t) {
+                    Frag8 bw;
+                    bw.q = *reinterpret_cast<const uint4 *>(&w1_lds[(t * 32 + i) * LDW1 + s * BK + 32 * h + 8 * c]);
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw.v, af.v, acc[t], 0, 0, 0);
+                }
+            }
+            wave_sync_lds();
+        }
+        // hidden tile -> operands of the second product
+        Frag8 hf[NT1 * 2];
+#pragma unroll
+        for (int t = 0; t < NT1; ++t)
+#pragma unroll
+            for (int qp = 0; qp < 2; ++qp) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int col = t * 32 + 16 * qp + 8 * (e / 4) + 4 * h + e % 4;
+                    v[e] = acc[t][8 * qp + e] + ((m.b1 && col < m.d_hid) ? m.b1[col] : 0.f);
+                    if (m.relu1) v[e] = v[e] > 0.f ? v[e] : 0.f;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) hf[t * 2 + qp].u[e] = f32_to_bf16_bits(v[2 * e]) | (f32_to_bf16_bits(v[2 * e + 1]) << 16);
+            }
+        f32x16 acc2[NT2];
+#pragma unroll
+        for (int t = 0; t < NT2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc2[t][r] = 0.f;
+#pragma unroll
+        for (int g = 0; g < NT1 * 2; ++g)
+#pragma unroll
+            for (int t = 0; t < NT2; ++t) {
+                Frag8 bw;
+                bw.q = *reinterpret_cast<const uint4 *>(&w2_lds[(t * 32 + i) * LDW2 + 16 * g + 8 * h]);
+                acc2[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw.v, hf[g].v, acc2[t], 0, 0, 0);
+            }
+        store_tile_lines<NT2, OUT_BF16>(pa, acc2, reinterpret_cast<float *>(abuf), tile * 32, lane);
+        tile += stride;
+    };
+    do_tile();
+    while (tile < n_tiles) do_tile();
+}
+
+template <int NS1, int NT2>
+hipError_t launch_mlp(const MlpArgs &m, bool out_bf16, int cus, hipStream_t s)
+{
+    constexpr int W1_BYTES = (128 * (NS1 * 64 + 8) * 2 + 15) / 16 * 16, W2_BYTES = (NT2 * 32 * 136 * 2 + 15) / 16 * 16;
+    const int wave_bytes = out_bf16 ? wave_lds_bytes<NT2, true>(32 * 72 * 2) : wave_lds_bytes<NT2, false>(32 * 72 * 2);
+    const size_t lds = static_cast<size_t>(W1_BYTES) + W2_BYTES + kMlpWaves * static_cast<size_t>(wave_bytes);
+    const int64_t want = ((m.n_rows + 31) / 32 + kMlpWaves - 1) / kMlpWaves;
+    const int blocks = static_cast<int>(want < cus ? want : cus);      // the LDS of a CU holds one workgroup
+    static bool raised[2] = {false, false};
+    if (out_bf16) {
+        if (!raised[1]) { (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&mlp_bf16_stream_kernel<NS1, NT2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)); raised[1] = true; }
+        hipLaunchKernelGGL((mlp_bf16_stream_kernel<NS1, NT2, true>), dim3(blocks), dim3(kMlpThreads), lds, s, m);
+    } else {
+        if (!raised[0]) { (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&mlp_bf16_stream_kernel<NS1, NT2, false>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)); raised[0] = true; }
+        hipLaunchKernelGGL((mlp_bf16_stream_kernel<NS1, NT2, false>), dim3(blocks), dim3(kMlpThreads), lds, s, m);
+    }
+    return hipGetLastError();
+}
+
 template <int NT, int NS>
 hipError_t launch_bf16(const UpdArgs &p, bool a_bf16, int cus, hipStream_t s)
 {
@@ -357,6 +506,27 @@ hipError_t launch_f32(const UpdArgs &p, int cus, hipStream_t s)
 }
 
 }  // namespace
+
+bool launch_mlp_stream(int64_t n_rows, const float *a, int64_t ld_a, int32_t d_in, const void *w1, const float *b1, mgg_act_t act1,
+                       int32_t d_hid, const void *w2, const float *b2, mgg_act_t act2, int32_t d_out, mgg_dtype_t out_dtype, void *out,
+                       int64_t ld_out, int cus, hipStream_t stream, hipError_t *err)
+{
+    // covered: fp32 A whose rows allow 16-byte loads, d_in = 64 or 128, 33..128 hidden and output columns,
+    // elementwise activations
+    if ((reinterpret_cast<uintptr_t>(a) & 15u) || ld_a % 4 || (d_in != 64 && d_in != 128)) return false;
+    if (d_hid <= 32 || d_hid > 128 || d_out <= 32 || d_out > 128) return false;
+    if ((act1 != MGG_ACT_NONE && act1 != MGG_ACT_RELU) || (act2 != MGG_ACT_NONE && act2 != MGG_ACT_RELU)) return false;
+    MlpArgs m{};
+    m.a = a; m.w1 = static_cast<const uint16_t *>(w1); m.w2 = static_cast<const uint16_t *>(w2); m.b1 = b1; m.b2 = b2; m.out = out;
+    m.n_rows = n_rows; m.ld_a = ld_a; m.ld_out = ld_out; m.d_in = d_in; m.d_hid = d_hid; m.d_out = d_out;
+    m.relu1 = act1 == MGG_ACT_RELU; m.relu2 = act2 == MGG_ACT_RELU;
+    const bool ob = out_dtype == MGG_BF16;
+    m.out_vec_ok = (ld_out % 4 == 0) && (reinterpret_cast<uintptr_t>(out) % (ob ? 8 : 16) == 0);
+    const int nt2 = d_out > 64 ? 4 : 2;
+    if (d_in == 64) *err = nt2 == 4 ? launch_mlp<1, 4>(m, ob, cus, stream) : launch_mlp<1, 2>(m, ob, cus, stream);
+    else *err = nt2 == 4 ? launch_mlp<2, 4>(m, ob, cus, stream) : launch_mlp<2, 2>(m, ob, cus, stream);
+    return true;
+}
 
 bool launch_update_stream(const upd::UpdArgs &p, bool w_bf16, bool a_bf16, int cus, hipStream_t stream, hipError_t *err)
 {

@@ -381,6 +381,46 @@ def test_update_softmax(n_rows, d_in, d_out, bf16):
     np.testing.assert_allclose(got.sum(axis=1), 1.0, rtol=1e-5)
 
 
+@pytest.mark.parametrize("n_rows,dims,acts,with_bias,out_bf16", [
+    (1000, (128, 128, 128), ("relu", "none"), False, False), (70001, (128, 128, 128), ("relu", "relu"), True, True),
+    (333, (64, 100, 47), ("relu", "none"), True, False), (31, (128, 40, 128), ("none", "relu"), True, False),
+    (515, (64, 128, 64), ("relu", "none"), False, True),
+    (200, (96, 128, 128), ("relu", "none"), True, False), (200, (128, 300, 64), ("relu", "none"), False, False)])
+def test_update_mlp(n_rows, dims, acts, with_bias, out_bf16):
+    """Two chained Updates with bf16 weights and fp32 input (GIN's MLP after the aggregation): the
+    one-kernel form where the shape allows (the last two shapes fall back to two launches), against the
+    oracle and against two separate mgg_update calls with a bf16 hidden buffer."""
+    rng = np.random.default_rng(sum(dims) + n_rows)
+    a = rng.standard_normal((n_rows, dims[0])).astype(np.float32)
+    w = [inputs.to_bf16_bits((0.1 * rng.standard_normal((dims[i], dims[i + 1]))).astype(np.float32)) for i in range(2)]
+    b = [rng.standard_normal(dims[i + 1]).astype(np.float32) if with_bias else None for i in range(2)]
+    hid_ref = oracle.update(a, w[0], b[0], acts[0])
+    ref = oracle.update(hid_ref, w[1], b[1], acts[1])
+    s = np.abs(a).astype(np.float64) @ np.abs(oracle.to_f64(w[0])) + (0 if b[0] is None else np.abs(b[0]))
+    s = s @ np.abs(oracle.to_f64(w[1])) + (0 if b[1] is None else np.abs(b[1]))
+    d_b = [None if x is None else to_dev(x) for x in b]
+    odt = torch.bfloat16 if out_bf16 else torch.float32
+    pad = 8 if out_bf16 else 4
+    buf = torch.full((n_rows, dims[2] + pad), float("nan"), dtype=odt, device=DEV)
+    hidden = torch.empty((n_rows, dims[1]), dtype=torch.bfloat16, device=DEV)
+    got = binding.mgg_update_mlp(to_dev(a), to_dev(w[0]), to_dev(w[1]), acts, d_b, hidden=hidden, out=buf[:, :dims[2]])
+    two = binding.mgg_update(binding.mgg_update(to_dev(a), to_dev(w[0]), d_b[0], acts[0], out_dtype=torch.bfloat16),
+                             to_dev(w[1]), d_b[1], acts[1], out_dtype=odt)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:, dims[2]:]).all()
+    assert_close(to_host64(got), ref, 2e-2, 2.0 ** -6 * s, f"mlp {dims}")
+    # same roundings as the two-call form, another summation order in the second product
+    assert_close(to_host64(got), to_host64(two), 2e-2 if out_bf16 else 1e-3, 2.0 ** (-7 if out_bf16 else -12) * s, f"mlp vs two calls {dims}")
+    covered = dims[0] in (64, 128) and 32 < dims[1] <= 128 and 32 < dims[2] <= 128
+    if covered:                                           # the one-kernel form needs no hidden buffer
+        again = binding.mgg_update_mlp(to_dev(a), to_dev(w[0]), to_dev(w[1]), acts, d_b, out_dtype=odt)
+        torch.cuda.synchronize()
+        assert torch.equal(again, got)
+    else:
+        with pytest.raises(binding.MggError):
+            binding.mgg_update_mlp(to_dev(a), to_dev(w[0]), to_dev(w[1]), acts, d_b, out_dtype=odt)
+
+
 # ----------------------------------------------------------------------------- whole layers on the five configs
 SHRINK = {1: 0, 2: 5, 3: 7, 4: 4, 5: 6}
 
