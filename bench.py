@@ -108,10 +108,11 @@ ABLATIONS = [
     ("no neighbour partitioning (a whole row per wavefront, section 7.2 'NP')", {"ps": 64, "dist": 1024, "xcd_min_deg": -1}, {}),
     ("no interleaving (local and remote lists in two launches, section 7.2 'WI')", {}, {"split_phases": 1}),
     ("no XCD-aware schedule", {"xcd_min_deg": -1}, {}),
+    ("source classes by hash (8 classes, one per XCD)", {"hot_phases": -1}, {}),
     ("no short-row bin", {"short_max": -1}, {}),
     ("halo rows staged through LDS", {}, {"lds_halo": 1}),
     ("no column slabs", {}, {"col_slab_bytes": 1}),
-    ("source classes by popularity, 4 hot phases per XCD, instead of by hash", {"hot_phases": 4}, {}),
+    ("source classes by popularity, 4 hot phases per XCD", {"hot_phases": 4}, {}),
 ]
 
 

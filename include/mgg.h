@@ -67,20 +67,21 @@ typedef struct {
     int32_t xcd_min_deg; /* rows with at least this many neighbours have their neighbour lists
                             regrouped by source class (see hot_rows), one piece of work per
                             class; 0 = library default, negative = no classes at all */
-    /* Source classes.  By default (hot_phases 0 or negative) a table row's class is a hash of
-     * its index, 8 classes, one per XCD.  With hot_phases >= 1 the rows of the two embedding
-     * tables are instead ranked by how many owned rows gather them; the 8 * hot_rows most
+    /* Source classes, two kinds.  By hash (hot_phases < 0): a table row's class is a hash of its
+     * index, 8 classes, one per XCD.  By popularity (hot_phases >= 1): the rows of the two
+     * embedding tables are ranked by how many owned rows gather them; the 8 * hot_rows most
      * gathered form phase 0 and are dealt round-robin to the 8 XCDs, the next 8 * hot_rows
      * phase 1, ...; the rest is cold.  Each XCD runs the work of its phase-0 class first, then
      * phase 1, ..., then cold work, so its L2 holds hot_rows table rows at a time, each gathered
-     * many times.  (Measured: this halves the L2 misses of the densest workload and changes its
-     * time by under 5 %, which is why it is not the default.) */
+     * many times.  hot_phases = 0 chooses: by popularity with 4 phases when the rows of phase 0
+     * would receive less than half of all gathers (gathers spread evenly: plain LRU keeps little
+     * of a hash class), by hash otherwise. */
     int32_t hot_row_bytes; /* bytes of one table row (or of one column slab of it) this schedule is
                               laid out for; sets hot_rows = 3 MB / (row bytes in whole 128-byte
                               lines) when hot_rows is 0; 0 = 256 */
     int32_t hot_rows;      /* table rows per XCD and phase; 0 = from hot_row_bytes */
-    int32_t hot_phases;    /* most phases (1..31); 0 or negative = 8 classes by a hash of the table
-                              row index instead of by popularity, no cold class */
+    int32_t hot_phases;    /* most phases (1..31); negative = 8 classes by a hash of the table row
+                              index, no cold class; 0 = automatic */
     int32_t min_piece;     /* a class with fewer neighbours than this in a row joins the row's
                               cold piece; 0 = default 16 */
     int32_t hot_min_count; /* table rows gathered fewer times than this are cold; 0 = default 8 */
@@ -92,6 +93,7 @@ typedef struct {
     int32_t num_parts, part_id;
     int32_t ps, dist, short_max, on_device;
     int32_t xcd_min_deg, wpb;
+    int32_t class_mode;                       /* source classes: 0 none, 1 by hash, 2 by popularity */
     int32_t hot_rows, n_phases;               /* table rows per XCD and phase; phases in use    */
     int32_t min_piece, hot_min_count;
     int64_t n_groups_local, n_groups_remote;  /* neighbour partitions of the two CSRs        */

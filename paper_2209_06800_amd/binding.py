@@ -53,6 +53,7 @@ class PartitionInfo(C.Structure):
                 ("num_parts", C.c_int32), ("part_id", C.c_int32),
                 ("ps", C.c_int32), ("dist", C.c_int32), ("short_max", C.c_int32), ("on_device", C.c_int32),
                 ("xcd_min_deg", C.c_int32), ("wpb", C.c_int32),
+                ("class_mode", C.c_int32),
                 ("hot_rows", C.c_int32), ("n_phases", C.c_int32), ("min_piece", C.c_int32), ("hot_min_count", C.c_int32),
                 ("n_groups_local", C.c_int64), ("n_groups_remote", C.c_int64),
                 ("n_short_rows", C.c_int64), ("n_items", C.c_int64),

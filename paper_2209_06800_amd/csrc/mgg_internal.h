@@ -36,7 +36,8 @@ struct SplitRow {
 constexpr int kXcd = 8;             // accelerator complex dies of an MI355X, each with its own L2
 constexpr int kDefaultWpb = 4;      // work items (wavefronts) per workgroup of the aggregation kernel
 constexpr int kDefaultXcdMinDeg = 256;
-constexpr int kDefaultHotPhases = -1;       // 8 classes by hash; popularity-ranked phases are opt-in
+constexpr int kDefaultHotPhases = 0;        // automatic choice between hash classes and popularity phases
+constexpr int kAutoHotPhases = 4;           // phases when the automatic choice takes popularity classes
 constexpr int kMaxHotPhases = 31;           // class index phase * 8 + XCD has to stay below kColdClass
 constexpr int kDefaultMinPiece = 16;        // a class with fewer neighbours in a row joins the row's cold piece
 constexpr int kDefaultHotMinCount = 8;      // table rows gathered fewer times than this are never hot
@@ -62,6 +63,7 @@ struct mgg_partition {
     int32_t num_parts = 1, part_id = 0;
     int32_t ps = 32, dist = 16, short_max = 16, xcd_min_deg = -1, wpb = 4;
     int32_t hot_rows = 0, hot_phases = 0, n_phases = 0, min_piece = 0, hot_min_count = 0;
+    int32_t class_mode = 0;           // 0: no source classes, 1: by hash, 2: by popularity
     std::vector<uint8_t> src_class;   // class of every table row (local rows, then halo slots); empty: no classes
     int device = -1;  // HIP device the arrays live on; -1 = host only
     std::vector<int32_t> local_row_ptr, local_col, remote_row_ptr, remote_col;

@@ -130,7 +130,7 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
     if (opts) {
         if (opts->hot_row_bytes) hot_row_bytes = opts->hot_row_bytes;
         if (opts->hot_rows) hot_rows = opts->hot_rows;
-        if (opts->hot_phases) hot_phases = opts->hot_phases;
+        hot_phases = opts->hot_phases;
         if (opts->min_piece) min_piece = opts->min_piece;
         if (opts->hot_min_count) hot_min_count = opts->hot_min_count;
         if (opts->ps) ps = opts->ps;
@@ -249,8 +249,8 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
         }
 
         // ---- source classes -------------------------------------------------------------
-        // Every row of the two embedding tables gets a class.  Default (hot_phases < 0): a hash of
-        // its index, 8 classes, one per XCD, no cold class.  With hot_phases >= 1 the class is
+        // Every row of the two embedding tables gets a class.  hot_phases < 0: a hash of its index, 8
+        // classes, one per XCD, no cold class.  With hot_phases >= 1 (0 chooses between the two) the class is
         // either (phase, XCD) -- "hot" -- or cold, and hot classes are filled in order of popularity (how many owned rows gather the
         // table row): the 8*hot_rows most gathered rows form phase 0, dealt round-robin to the
         // 8 XCDs, the next 8*hot_rows phase 1, and so on.  An XCD works through its phases in
@@ -261,22 +261,36 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
         int n_phase = 0;
         if (use_classes) {
             p->src_class.assign(static_cast<size_t>(n_tab), kColdClass);
+            std::vector<int32_t> order;                          // table rows, most gathered first
+            std::vector<int32_t> cnt;
+            const int64_t per_phase = static_cast<int64_t>(kXcd) * hot_rows;
+            if (hot_phases >= 0 && n_tab > 0) {
+                cnt.assign(static_cast<size_t>(n_tab), 0);
+                for (int32_t u : p->local_col) ++cnt[u];
+                for (int32_t u : p->remote_col) ++cnt[n_own + u];
+                // counting sort by gather count (ties: lower index first)
+                const int32_t max_cnt = *std::max_element(cnt.begin(), cnt.end());
+                std::vector<int64_t> start(static_cast<size_t>(max_cnt) + 2, 0);
+                for (int64_t i = 0; i < n_tab; ++i) ++start[max_cnt - cnt[i] + 1];
+                for (size_t c = 1; c < start.size(); ++c) start[c] += start[c - 1];
+                order.resize(static_cast<size_t>(n_tab));
+                for (int64_t i = 0; i < n_tab; ++i) order[start[max_cnt - cnt[i]]++] = static_cast<int32_t>(i);
+            }
+            if (hot_phases == 0) {
+                // Automatic.  The hash classes win while L2 can hold what matters of a class under plain LRU;
+                // when gathers are spread so evenly that the most gathered rows of one phase get less than
+                // half of them (measured: the 2.4 M-node R-MAT of the configs, 41 %, 4-8 % faster with
+                // phases; the others, 69-86 %, 5-10 % slower), explicit hot phases do better.
+                int64_t top = 0, all = static_cast<int64_t>(p->local_col.size()) + static_cast<int64_t>(p->remote_col.size());
+                for (int64_t r = 0; r < std::min<int64_t>(n_tab, per_phase); ++r) top += cnt[order[r]];
+                hot_phases = (all > 0 && 2 * top < all) ? kAutoHotPhases : -1;
+            }
+            p->class_mode = hot_phases < 0 ? 1 : 2;
             if (hot_phases < 0) {
                 n_phase = 1;
                 for (int64_t i = 0; i < n_own; ++i) p->src_class[i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
                 for (int64_t i = 0; i < num_halo; ++i) p->src_class[n_own + i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
             } else if (n_tab > 0) {
-                std::vector<int32_t> cnt(static_cast<size_t>(n_tab), 0);
-                for (int32_t u : p->local_col) ++cnt[u];
-                for (int32_t u : p->remote_col) ++cnt[n_own + u];
-                // counting sort of the table rows by gather count, most gathered first (ties: lower index first)
-                const int32_t max_cnt = *std::max_element(cnt.begin(), cnt.end());
-                std::vector<int64_t> start(static_cast<size_t>(max_cnt) + 2, 0);
-                for (int64_t i = 0; i < n_tab; ++i) ++start[max_cnt - cnt[i] + 1];
-                for (size_t c = 1; c < start.size(); ++c) start[c] += start[c - 1];
-                std::vector<int32_t> order(static_cast<size_t>(n_tab));
-                for (int64_t i = 0; i < n_tab; ++i) order[start[max_cnt - cnt[i]]++] = static_cast<int32_t>(i);
-                const int64_t per_phase = static_cast<int64_t>(kXcd) * hot_rows;
                 const int64_t limit = std::min<int64_t>(n_tab, per_phase * hot_phases);
                 int64_t r = 0;
                 for (; r < limit && cnt[order[r]] >= hot_min_count; ++r)
@@ -419,6 +433,7 @@ mgg_status_t mgg_partition_info(const mgg_partition_t *p, mgg_partition_info_t *
     o->num_parts = p->num_parts; o->part_id = p->part_id;
     o->ps = p->ps; o->dist = p->dist; o->short_max = p->short_max; o->on_device = p->device >= 0;
     o->xcd_min_deg = p->xcd_min_deg; o->wpb = p->wpb;
+    o->class_mode = p->class_mode;
     o->hot_rows = p->hot_rows; o->n_phases = p->n_phases; o->min_piece = p->min_piece; o->hot_min_count = p->hot_min_count;
     o->n_groups_local = p->n_groups_local; o->n_groups_remote = p->n_groups_remote;
     o->n_short_rows = static_cast<int64_t>(p->short_rows.size());

@@ -42,7 +42,14 @@ def _compare_with_oracle(row_ptr, col, parts, p, bounds, **opts):
         assert np.array_equal(got[f"grp_{kind}_row"], row)
         assert np.array_equal(got[f"grp_{kind}_start"], start)
         assert np.array_equal(got[f"grp_{kind}_end"], end)
-    _check_schedule(got, info, hot_by_popularity=opts.get("hot_phases", 0) > 0)
+    hp = opts.get("hot_phases", 0)
+    if opts.get("xcd_min_deg", 0) < 0:
+        assert info.class_mode == 0
+    elif hp != 0:
+        assert info.class_mode == (2 if hp > 0 else 1)
+    else:
+        assert info.class_mode in (1, 2)                     # the library chooses
+    _check_schedule(got, info, hot_by_popularity=info.class_mode == 2)
     part.destroy()
     return got, info
 
@@ -301,3 +308,26 @@ def test_layer_workspace_bytes_follow_the_order():
     assert need((100, 40), binding.ORDER_AUTO) == max(need((100, 40), binding.ORDER_AGG_FIRST), need((100, 40), binding.ORDER_UPDATE_FIRST))
     assert need((100, 90), binding.ORDER_AUTO) == need((100, 90), binding.ORDER_AGG_FIRST)
     assert need((100, 40), 7) == 0 and need((100, 0), 0) == 0 and need((100,), 0) == 0
+
+
+def test_automatic_choice_of_source_classes():
+    """hot_phases = 0: popularity phases when the most gathered rows of one phase receive less than
+    half of all gathers, hash classes otherwise."""
+    rng = np.random.default_rng(8)
+    # skewed: R-MAT hubs take most gathers -> by hash
+    row_ptr, col = inputs.rmat_graph(12, 60000, 0.57, 0.19, 0.19, 0.05, rng)
+    part = binding.mgg_build_partition(row_ptr, col, 2, 0, None, host_only=True, hot_rows=8, xcd_min_deg=8)
+    cnt = np.sort(np.bincount(np.concatenate([part.export()["local_col"], part.info.n_own + part.export()["remote_col"]])))[::-1]
+    share = cnt[:64].sum() / cnt.sum()
+    assert part.info.class_mode == (2 if share < 0.5 else 1)
+    # flat: a random regular-ish graph, every row gathered about equally often -> by popularity
+    n = 4096
+    col2 = rng.integers(0, n, size=n * 16).astype(np.int32)
+    row_ptr2 = np.arange(0, n * 16 + 1, 16, dtype=np.int64)
+    part2 = binding.mgg_build_partition(row_ptr2, col2, 1, 0, None, host_only=True, hot_rows=8, xcd_min_deg=8)
+    assert part2.info.class_mode == 2 and part2.info.n_phases == 4
+    # skewed by construction: 64 hub rows take nine tenths of the gathers -> by hash
+    hub = rng.integers(0, 64, size=n * 16)
+    col3 = np.where(rng.random(n * 16) < 0.9, hub, col2).astype(np.int32)
+    part3 = binding.mgg_build_partition(row_ptr2, col3, 1, 0, None, host_only=True, hot_rows=8, xcd_min_deg=8)
+    assert part3.info.class_mode == 1
