@@ -613,3 +613,33 @@ def test_update_first_matches_the_oracle(mode, bf16, dims, acts, with_bias):
         for order in got:
             assert_close(got[order], ref, 2e-2 if bf16 else 1e-4, bound, f"{mode} {dims} part {p} {order}")
         part.destroy()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_aggregate_random_graphs_and_schedules(seed):
+    """Seeded random cases: small graphs with hubs, duplicates, self-loops and empty rows, random
+    widths, dtypes, modes, shares and schedule knobs."""
+    rng = np.random.default_rng(9000 + seed)
+    n = int(rng.integers(2, 400))
+    hubs = rng.integers(0, n, size=3)
+    rows = []
+    for v in range(n):
+        d = int(rng.choice([0, 1, 3, 17, 40, 300 if v in hubs else 5]))
+        rows.append(sorted(rng.integers(0, n, size=d).tolist()))
+    row_ptr, col = inputs.csr_from_adjacency_lists(rows)
+    parts = int(rng.integers(1, 5))
+    bounds = np.array([0] + sorted(rng.integers(0, n + 1, size=parts - 1).tolist()) + [n], dtype=np.int64)
+    dim = int(rng.choice([1, 5, 16, 47, 64, 100, 130, 256, 602]))
+    bf16 = bool(rng.integers(0, 2))
+    mode = str(rng.choice(["gcn", "gin"]))
+    x = rng.standard_normal((n, dim)).astype(np.float32)
+    if bf16:
+        x = inputs.to_bf16_bits(x)
+    build = dict(ps=int(rng.choice([1, 4, 32, 64])), dist=int(rng.choice([1, 2, 16])), short_max=int(rng.choice([-1, 2, 16])),
+                 wpb=int(rng.choice([1, 4, 8])), xcd_min_deg=int(rng.choice([-1, 1, 20, 256])),
+                 hot_phases=int(rng.choice([-1, 0, 2])), hot_rows=int(rng.choice([0, 3, 50])), min_piece=int(rng.choice([1, 4, 16])))
+    ld_pad = int(rng.choice([0, 0, 3, 8]))
+    for p in range(parts):
+        if bounds[p + 1] > bounds[p]:
+            check_aggregate(row_ptr, col, parts, p, bounds, x, mode, eps=float(rng.choice([0.0, 0.5, -1.0])), build=build,
+                            ld_pad=ld_pad, what=f"seed {seed} part {p} dim {dim} {build}")

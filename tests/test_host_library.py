@@ -331,3 +331,29 @@ def test_automatic_choice_of_source_classes():
     col3 = np.where(rng.random(n * 16) < 0.9, hub, col2).astype(np.int32)
     part3 = binding.mgg_build_partition(row_ptr2, col3, 1, 0, None, host_only=True, hot_rows=8, xcd_min_deg=8)
     assert part3.info.class_mode == 1
+
+
+def test_partition_fuzz_against_oracle():
+    """Random small graphs (duplicates, self-loops, empty rows, directed), random bounds (empty ranges
+    allowed) and random schedule knobs: integer structures bit-exact against the oracle's builder, and a
+    valid schedule whatever the knobs."""
+    from hypothesis import given, settings, strategies as st, HealthCheck
+
+    @settings(max_examples=80, deadline=None, suppress_health_check=list(HealthCheck), derandomize=True)
+    @given(st.data())
+    def run(data):
+        n = data.draw(st.integers(1, 48))
+        rows = [data.draw(st.lists(st.integers(0, n - 1), max_size=data.draw(st.sampled_from([0, 2, 5, 40])))) for _ in range(n)]
+        row_ptr, col = inputs.csr_from_adjacency_lists([sorted(r) for r in rows])
+        parts = data.draw(st.integers(1, 5))
+        cuts = sorted(data.draw(st.lists(st.integers(0, n), min_size=parts - 1, max_size=parts - 1)))
+        bounds = np.array([0] + cuts + [n], dtype=np.int64)
+        opts = dict(ps=data.draw(st.sampled_from([1, 2, 7, 32, 64])), dist=data.draw(st.sampled_from([1, 2, 16])),
+                    short_max=data.draw(st.sampled_from([-1, 1, 3, 16])), wpb=data.draw(st.sampled_from([1, 4, 16])),
+                    xcd_min_deg=data.draw(st.sampled_from([-1, 1, 4, 30])),
+                    hot_phases=data.draw(st.sampled_from([-1, 0, 1, 3, 31])), hot_rows=data.draw(st.sampled_from([1, 2, 5, 100])),
+                    min_piece=data.draw(st.sampled_from([1, 2, 9])), hot_min_count=data.draw(st.sampled_from([1, 2, 4])))
+        for p in range(parts):
+            _compare_with_oracle(row_ptr, col, parts, p, bounds, **opts)
+
+    run()
