@@ -300,12 +300,12 @@ mgg_status_t mgg_tune_aggregate(int64_t num_nodes, const int64_t *row_ptr, const
                                 mgg_tuner_t *tuner, mgg_knobs_t *best, double *best_ms);
 
 /* Run-time switches for experiments (ablations of section 7.2's kind).  Known keys:
- *   "xcd_remap"   0/1  contiguous chunks of work items per XCD            (default 1)
  *   "lds_halo"    0/1  stage halo rows through LDS ahead of accumulation  (default 0)
  *   "split_phases" 0/1 aggregate the local lists and the remote lists in two launches, the
  *                      second adding to the first (no interleaving; default 0)
- *   "update_stream" 0/1 Update shapes with whole K slabs and 33..128 output columns take the
- *                      whole-line kernels (default 1; 0 = the register-resident kernels)
+ *   "update_stream" 0/1 the Update kernels added for streaming efficiency (whole-line kernels, the
+ *                      one-kernel MLP, two W slabs in LDS) are used where they apply (default 1;
+ *                      0 = the plain register-resident and slab kernels everywhere)
  *   "col_slab_bytes"   0 = automatic (default), 1 = off, or a power of two in [64, 4096]:
  *                      bytes of an embedding row handled per pass over the work items
  * Unknown key or bad value -> MGG_ERR_INVALID_ARG.  Not thread-safe against running calls. */

@@ -7,12 +7,10 @@
 
 namespace mgg {
 
-static std::atomic<int32_t> g_xcd_remap{0};
 static std::atomic<int32_t> g_lds_halo{0};
 static std::atomic<int32_t> g_col_slab_bytes{0};
 static std::atomic<int32_t> g_split_phases{0};
 static std::atomic<int32_t> g_update_stream{1};
-int32_t option_xcd_remap() { return g_xcd_remap.load(); }
 int32_t option_lds_halo() { return g_lds_halo.load(); }
 int32_t option_col_slab_bytes() { return g_col_slab_bytes.load(); }
 int32_t option_split_phases() { return g_split_phases.load(); }
@@ -236,7 +234,6 @@ mgg_status_t mgg_set_option(const char *key, int32_t value)
         return MGG_OK;
     }
     if (value != 0 && value != 1) return fail(MGG_ERR_INVALID_ARG, "option value must be 0 or 1");
-    if (!std::strcmp(key, "xcd_remap")) { g_xcd_remap = value; return MGG_OK; }
     if (!std::strcmp(key, "lds_halo")) { g_lds_halo = value; return MGG_OK; }
     if (!std::strcmp(key, "split_phases")) { g_split_phases = value; return MGG_OK; }
     if (!std::strcmp(key, "update_stream")) { g_update_stream = value; return MGG_OK; }
@@ -246,7 +243,6 @@ mgg_status_t mgg_set_option(const char *key, int32_t value)
 mgg_status_t mgg_get_option(const char *key, int32_t *value)
 {
     if (!key || !value) return fail(MGG_ERR_INVALID_ARG, "NULL argument");
-    if (!std::strcmp(key, "xcd_remap")) { *value = g_xcd_remap; return MGG_OK; }
     if (!std::strcmp(key, "lds_halo")) { *value = g_lds_halo; return MGG_OK; }
     if (!std::strcmp(key, "col_slab_bytes")) { *value = g_col_slab_bytes; return MGG_OK; }
     if (!std::strcmp(key, "split_phases")) { *value = g_split_phases; return MGG_OK; }

@@ -90,7 +90,6 @@ mgg_status_t hip_fail(hipError_t e, const char *what);
         if (_e != hipSuccess) return ::mgg::hip_fail(_e, #expr); \
     } while (0)
 
-int32_t option_xcd_remap();
 int32_t option_lds_halo();
 int32_t option_col_slab_bytes();
 int32_t option_split_phases();

@@ -269,7 +269,7 @@ def test_device_calls_refuse_a_host_only_partition():
 
 
 def test_options_round_trip():
-    for key in ("xcd_remap", "lds_halo"):
+    for key in ("split_phases", "lds_halo", "update_stream"):
         old = binding.mgg_get_option(key)
         binding.mgg_set_option(key, 1 - old)
         assert binding.mgg_get_option(key) == 1 - old
