@@ -403,53 +403,65 @@ __global__ __launch_bounds__(kWave * kMaxWpb) void aggregate_kernel(const AggArg
     }
 }
 
-// Rows cut into several items: one workgroup per such row adds its partial sums in a fixed
-// order (wave w takes slots w, w+4, ... front to back; the four wave sums are then added
-// 0+1+2+3), adds the self term and the row factor, and writes the row.  64 columns at a time.
+// Rows cut into several items: one wavefront per such row adds its partial sums slot by slot, front
+// to back (a fixed order: results do not depend on scheduling), adds the self term and the row
+// factor, and writes the row.  Scratch rows start on 32-byte boundaries, so every lane takes four
+// consecutive columns with one 16-byte load per slot, several slots in flight; no LDS, no barrier.
 template <bool BF16>
-__global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_rows, int32_t dim, const float *scratch,
+__global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_rows, int32_t n_split, int32_t dim, const float *scratch,
                                                        int64_t scratch_ld, const void *x_local, int64_t ld_x,
                                                        const float *dinv_own, int32_t gcn, float self_w, float *out,
-                                                       int64_t ld_out, int32_t phase, const float *bias, int32_t relu)
+                                                       int64_t ld_out, int32_t out_vec_ok, int32_t phase, const float *bias, int32_t relu)
 {
-    __shared__ float part[kWavesPerBlock][kWave];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const SplitRow sr = split_rows[blockIdx.x];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int r_id = static_cast<int>(blockIdx.x) * kWavesPerBlock + static_cast<int>(threadIdx.x / kWave);
+    if (r_id >= n_split) return;
+    const SplitRow sr = split_rows[r_id];
     const float dv = gcn ? dinv_own[sr.row] : 1.f;
     const float ws = gcn ? dv : self_w;
-    for (int k0 = 0; k0 < dim; k0 += kWave) {
-        const int k = k0 + lane;
-        float sum = 0.f;
-        if (k < dim) {
-            const float *src = scratch + static_cast<int64_t>(sr.first_slot) * scratch_ld + k;
-            int i = wave;
-            for (; i + 3 * kWavesPerBlock < sr.n_slots; i += 4 * kWavesPerBlock) {
-                const float v0 = src[static_cast<int64_t>(i) * scratch_ld];
-                const float v1 = src[static_cast<int64_t>(i + kWavesPerBlock) * scratch_ld];
-                const float v2 = src[static_cast<int64_t>(i + 2 * kWavesPerBlock) * scratch_ld];
-                const float v3 = src[static_cast<int64_t>(i + 3 * kWavesPerBlock) * scratch_ld];
-                sum = (((sum + v0) + v1) + v2) + v3;
-            }
-            for (; i < sr.n_slots; i += kWavesPerBlock) sum += src[static_cast<int64_t>(i) * scratch_ld];
+    const float *base = scratch + static_cast<int64_t>(sr.first_slot) * scratch_ld;
+    for (int k = 4 * lane; k < dim; k += 4 * kWave) {
+        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+        const float *src = base + k;                 // columns k .. k+3 exist in scratch (its rows are padded to 8)
+        int i = 0;
+        for (; i + 3 < sr.n_slots; i += 4) {
+            const float4 v0 = *reinterpret_cast<const float4 *>(src + static_cast<int64_t>(i) * scratch_ld);
+            const float4 v1 = *reinterpret_cast<const float4 *>(src + static_cast<int64_t>(i + 1) * scratch_ld);
+            const float4 v2 = *reinterpret_cast<const float4 *>(src + static_cast<int64_t>(i + 2) * scratch_ld);
+            const float4 v3 = *reinterpret_cast<const float4 *>(src + static_cast<int64_t>(i + 3) * scratch_ld);
+            sum.x = (((sum.x + v0.x) + v1.x) + v2.x) + v3.x; sum.y = (((sum.y + v0.y) + v1.y) + v2.y) + v3.y;
+            sum.z = (((sum.z + v0.z) + v1.z) + v2.z) + v3.z; sum.w = (((sum.w + v0.w) + v1.w) + v2.w) + v3.w;
         }
-        part[wave][lane] = sum;
-        __syncthreads();
-        if (wave == 0 && k < dim) {
-            const float total = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
-            float xv;
-            if constexpr (BF16)
-                xv = __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k]) << 16);
-            else
-                xv = static_cast<const float *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k];
-            float *o = out + static_cast<int64_t>(sr.row) * ld_out + k;
-            float r = phase == 2 ? *o + dv * total : dv * (total + ws * xv);
-            if (phase != 1) {
-                if (bias) r += bias[k];
-                if (relu) r = fmaxf(r, 0.f);
-            }
-            *o = r;
+        for (; i < sr.n_slots; ++i) {
+            const float4 v = *reinterpret_cast<const float4 *>(src + static_cast<int64_t>(i) * scratch_ld);
+            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
         }
-        __syncthreads();
+        const float total[4] = {sum.x, sum.y, sum.z, sum.w};
+        float *o = out + static_cast<int64_t>(sr.row) * ld_out + k;
+        float r[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            r[e] = 0.f;
+            if (k + e < dim) {
+                float xv;
+                if constexpr (BF16)
+                    xv = __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k + e]) << 16);
+                else
+                    xv = static_cast<const float *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k + e];
+                r[e] = phase == 2 ? o[e] + dv * total[e] : dv * (total[e] + ws * xv);
+                if (phase != 1) {
+                    if (bias) r[e] += bias[k + e];
+                    if (relu) r[e] = fmaxf(r[e], 0.f);
+                }
+            }
+        }
+        if (out_vec_ok && k + 3 < dim) {
+            *reinterpret_cast<float4 *>(o) = make_float4(r[0], r[1], r[2], r[3]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (k + e < dim) o[e] = r[e];
+        }
     }
 }
 
@@ -594,12 +606,14 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
         }
         const int32_t n_split = static_cast<int32_t>(p->split_rows.size());
         if (n_split > 0) {
+            const dim3 fgrid(static_cast<unsigned>((n_split + kWavesPerBlock - 1) / kWavesPerBlock));
+            const int32_t fix_vec_ok = (ld_out % 4 == 0) && aligned(out, 16);
             if (bf16)
-                hipLaunchKernelGGL(fixup_kernel<true>, dim3(n_split), dim3(kBlock), 0, stream, p->d.split_rows, out_dim,
-                                   p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out, a.phase, bias, a.relu);
+                hipLaunchKernelGGL(fixup_kernel<true>, fgrid, dim3(kBlock), 0, stream, p->d.split_rows, n_split, out_dim, p->d.scratch,
+                                   p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out, fix_vec_ok, a.phase, bias, a.relu);
             else
-                hipLaunchKernelGGL(fixup_kernel<false>, dim3(n_split), dim3(kBlock), 0, stream, p->d.split_rows, out_dim,
-                                   p->d.scratch, p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out, a.phase, bias, a.relu);
+                hipLaunchKernelGGL(fixup_kernel<false>, fgrid, dim3(kBlock), 0, stream, p->d.split_rows, n_split, out_dim, p->d.scratch,
+                                   p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out, fix_vec_ok, a.phase, bias, a.relu);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return hip_fail(e, "fix-up kernel launch");
         }
