@@ -53,7 +53,7 @@ typedef struct mgg_partition mgg_partition_t;   /* opaque, library-owned */
  * ps = neighbours per neighbour partition (1..64), dist = how many (local, remote)
  * partition pairs one wavefront work item covers (1..1024), wpb = wavefronts per workgroup
  * (the paper's warps per block).  0 selects the default
- * (ps 32, dist 16, short_max 16, xcd_min_deg 256).  Rows with at most short_max neighbours in total
+ * (ps 64 -- one neighbour id per lane of a 64-lane wavefront --, dist 8, short_max 16, xcd_min_deg 256).  Rows with at most short_max neighbours in total
  * are handled several per wavefront; short_max < 0 disables that bin. */
 typedef struct {
     int32_t ps;

@@ -61,7 +61,7 @@ struct DeviceArrays {
 struct mgg_partition {
     int64_t num_nodes = 0, lb = 0, ub = 0, n_own = 0;
     int32_t num_parts = 1, part_id = 0;
-    int32_t ps = 32, dist = 16, short_max = 16, xcd_min_deg = -1, wpb = 4;
+    int32_t ps = 64, dist = 8, short_max = 16, xcd_min_deg = -1, wpb = 4;
     int32_t hot_rows = 0, hot_phases = 0, n_phases = 0, min_piece = 0, hot_min_count = 0;
     int32_t class_mode = 0;           // 0: no source classes, 1: by hash, 2: by popularity
     std::vector<uint8_t> src_class;   // class of every table row (local rows, then halo slots); empty: no classes

@@ -124,7 +124,7 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
     if (num_nodes > INT32_MAX - 1) return fail(MGG_ERR_UNSUPPORTED, "more than 2^31-2 nodes");
     if (num_parts < 1 || part_id < 0 || part_id >= num_parts)
         return fail(MGG_ERR_INVALID_ARG, "part_id %d outside [0, %d)", part_id, num_parts);
-    int32_t ps = 32, dist = 16, short_max = 16, host_only = 0, xcd_min_deg = kDefaultXcdMinDeg, wpb = kDefaultWpb;
+    int32_t ps = 64, dist = 8, short_max = 16, host_only = 0, xcd_min_deg = kDefaultXcdMinDeg, wpb = kDefaultWpb;
     int32_t hot_rows = 0, hot_phases = kDefaultHotPhases, min_piece = kDefaultMinPiece, hot_min_count = kDefaultHotMinCount;
     int32_t hot_row_bytes = 256;
     if (opts) {
