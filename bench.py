@@ -319,7 +319,7 @@ def run_update_shapes(iters: int = 20, vendor: bool = True):
     tdt = {"f32": torch.float32, "bf16": torch.bfloat16}
     rows = []
     for name, n, k, m, adt, wdt, odt in UPDATE_SHAPES:
-        a = torch.randn(n, k, device=dev).to(tdt[adt])
+        a = torch.randn(n, (k + 7) // 8 * 8, device=dev).to(tdt[adt])[:, :k]     # rows start on 16-byte boundaries
         w = (torch.randn(k, m, device=dev) * 0.1).to(tdt[wdt])
         out = torch.empty(n, m, device=dev, dtype=tdt[odt])
 
@@ -339,7 +339,7 @@ def run_update_shapes(iters: int = 20, vendor: bool = True):
         r = {"shape": name, "rows": n, "d_in": k, "d_out": m, "dtypes": f"{adt}/{wdt}/{odt}", "us": round(ms * 1e3, 1),
              "tflops": round(2.0 * n * k * m / ms / 1e9, 1), "gbs": round(byts / ms / 1e6)}
         if vendor:
-            av, wv = a.to(tdt[wdt]), w
+            av, wv = a.to(tdt[wdt]).contiguous(), w
             ov = torch.empty(n, m, device=dev, dtype=tdt[wdt])
             r["vendor_us"] = round(timed(lambda: torch.matmul(av, wv, out=ov)) * 1e3, 1)
         rows.append(r)
@@ -416,7 +416,8 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
             xh = to_dev(inputs.layer2_halo_table(w.notes["layer2_halo_seed"], int(info.num_halo), d_in), dev)
             lesz = 4
         ws = [to_dev(m, dev) for m in layer.weights]
-        agg = torch.empty((int(info.n_own), d_in), dtype=torch.float32, device=dev)
+        # the aggregation result is laid out as mgg_layer_forward lays it out: rows start on 32-byte boundaries
+        agg = torch.empty((int(info.n_own), (d_in + 7) // 8 * 8), dtype=torch.float32, device=dev)[:, :d_in]
         hid = None
         if len(ws) == 2:
             hid = torch.empty((int(info.n_own), layer.dims[1]), dtype=torch.bfloat16 if bf16 else torch.float32, device=dev)

@@ -35,6 +35,20 @@ __device__ __forceinline__ void load_a_f32(const UpdArgs &p, const float *arow, 
             const float4 v = *reinterpret_cast<const float4 *>(arow + kb + 4 * q);
             af[4 * q] = v.x; af[4 * q + 1] = v.y; af[4 * q + 2] = v.z; af[4 * q + 3] = v.w;
         }
+    } else if (p.a_vec_ok) {
+        // the last, incomplete slab of aligned rows: whole 16-byte pieces as long as they start inside the
+        // row (the leading dimension is a multiple of 4, so such a piece ends inside it too), then the
+        // elements past d_in -- padding of the row -- are cleared
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int k = kb + 4 * q;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < p.d_in) v = *reinterpret_cast<const float4 *>(arow + k);
+            af[4 * q] = v.x;
+            af[4 * q + 1] = k + 1 < p.d_in ? v.y : 0.f;
+            af[4 * q + 2] = k + 2 < p.d_in ? v.z : 0.f;
+            af[4 * q + 3] = k + 3 < p.d_in ? v.w : 0.f;
+        }
     } else {
 #pragma unroll
         for (int e = 0; e < 16; ++e) af[e] = (kb + e < p.d_in) ? arow[kb + e] : 0.f;
@@ -139,13 +153,20 @@ void update_f32_db_kernel(const UpdArgs p)
             load_w(k0 + BK);
             load_a_f32(p, arow, k0 + BK + 16 * h, k0 + 2 * BK, an);
         }
-        const float *wbuf = w_lds + cur * (BK * NC);
+        // W fragments are read from LDS one MFMA group ahead, so that the matrix pipe never waits for them
+        const float *wbuf = w_lds + cur * (BK * NC) + (16 * h) * NC + wn * NT * 32 + i;
+        float wf[2][NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) wf[0][t] = wbuf[t * 32];
 #pragma unroll
         for (int c = 0; c < 16; ++c) {
-            const float *wrow = wbuf + (16 * h + c) * NC + wn * NT * 32 + i;
+            if (c + 1 < 16) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) wf[(c + 1) & 1][t] = wbuf[(c + 1) * NC + t * 32];
+            }
 #pragma unroll
             for (int t = 0; t < NT; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(wrow[t * 32], af[c], acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[c & 1][t], af[c], acc[t], 0, 0, 0);
         }
         if (more) {
             store_w(w_lds + (cur ^ 1) * (BK * NC));
