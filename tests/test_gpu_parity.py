@@ -643,3 +643,47 @@ def test_aggregate_random_graphs_and_schedules(seed):
         if bounds[p + 1] > bounds[p]:
             check_aggregate(row_ptr, col, parts, p, bounds, x, mode, eps=float(rng.choice([0.0, 0.5, -1.0])), build=build,
                             ld_pad=ld_pad, what=f"seed {seed} part {p} dim {dim} {build}")
+
+
+# ----------------------------------------------------------------------------- HIP graph capture
+def test_layer_forward_in_a_hip_graph():
+    """After one eager call (which sizes the partition's scratch buffer) a layer forward allocates
+    nothing, synchronises nothing and records no memset, so it can be captured in a HIP graph.  Every
+    replay -- with new inputs, and with eager work and synchronisations in between -- must reproduce
+    the eager result bit for bit."""
+    w = inputs.config(2, shrink=5)
+    part = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
+    hg = part.export()["halo_gid"]
+    layer = w.layers[0]
+    xl, xh = to_dev(w.x[w.lb:w.ub]), to_dev(w.x[hg])
+    ws = [to_dev(m) for m in layer.weights]
+    wsp = torch.empty(binding.mgg_layer_workspace_bytes(part, layer.mode, ws, layer.acts), dtype=torch.uint8, device=DEV)
+    out = torch.empty((int(part.info.n_own), layer.dims[-1]), device=DEV)
+    side = torch.empty(1 << 20, device=DEV)
+
+    def forward():
+        binding.mgg_layer_forward(part, layer.mode, xl, xh, ws, layer.acts, workspace=wsp, out=out)
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        forward()                                   # eager: grows the scratch buffer
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        forward()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4)
+    for rep in range(4):
+        xl.copy_(to_dev(rng.standard_normal(tuple(xl.shape)).astype(np.float32)))
+        xh.copy_(to_dev(rng.standard_normal(tuple(xh.shape)).astype(np.float32)))
+        with torch.cuda.stream(stream):
+            forward()
+        torch.cuda.synchronize()
+        want = out.clone()
+        out.fill_(float("nan"))
+        side.normal_()                              # unrelated eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"replay {rep} differs from the eager result"
+    part.destroy()
