@@ -12,6 +12,11 @@
 //     both with fp32 accumulators; bias, ReLU and the output rounding are fused.
 // MFMA sums over k in any order, so a lane takes whichever k values are contiguous for it in
 // memory as long as the A and W operands agree; that makes the direct loads of A full-width.
+//
+// launch_update picks per shape: the whole-line kernels of update_stream.hip where they apply
+// (HBM-bound shapes with whole K slabs), the kernels of this file otherwise -- weights resident in
+// LDS with a grid sized to the chip, or staged slab by slab (two slabs in LDS for the fp32 MFMA).
+// Row softmax runs as a second pass over the output.
 #include <hip/hip_runtime.h>
 
 #include "update_common.h"
