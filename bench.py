@@ -61,12 +61,13 @@ def to_dev(a, dev, pad_rows_to_bytes=0):
     return t
 
 
-def gather_model_bytes(nnz, n_own, dim, elem_bytes, gcn):
+def gather_model_bytes(nnz, n_own, dim, elem_bytes, gcn, out_bytes=4):
     """Algorithmic bytes of one aggregation launch: per neighbour one embedding row, its 4-byte
     id and (GCN) the 4-byte normalisation factor of the neighbour; per owned row its own
-    embedding, the fp32 output row, two row-pointer entries and its normalisation factor."""
+    embedding, the output row (fp32, or bf16 ahead of a bf16 MFMA), two row-pointer entries and its
+    normalisation factor."""
     per_edge = dim * elem_bytes + 4 + (4 if gcn else 0)
-    per_row = dim * elem_bytes + dim * 4 + 12
+    per_row = dim * elem_bytes + dim * out_bytes + 12
     return nnz * per_edge + n_own * per_row
 
 
@@ -416,14 +417,16 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
             xh = to_dev(inputs.layer2_halo_table(w.notes["layer2_halo_seed"], int(info.num_halo), d_in), dev)
             lesz = 4
         ws = [to_dev(m, dev) for m in layer.weights]
-        # the aggregation result is laid out as mgg_layer_forward lays it out: rows start on 32-byte boundaries
-        agg = torch.empty((int(info.n_own), (d_in + 7) // 8 * 8), dtype=torch.float32, device=dev)[:, :d_in]
+        # the aggregation result is laid out as mgg_layer_forward lays it out: rows start on 32-byte boundaries,
+        # fp32 -- or bf16 when the weights are bf16 (the bf16 MFMA rounds its input the same way)
+        agg_dt = torch.bfloat16 if bf16 else torch.float32
+        agg = torch.empty((int(info.n_own), (d_in + 7) // 8 * 8), dtype=agg_dt, device=dev)[:, :d_in]
         hid = None
         if len(ws) == 2:
             hid = torch.empty((int(info.n_own), layer.dims[1]), dtype=torch.bfloat16 if bf16 else torch.float32, device=dev)
         out = torch.empty((int(info.n_own), layer.dims[-1]), dtype=torch.float32, device=dev)
         layers.append(dict(layer=layer, xl=xl, xh=xh, ws=ws, agg=agg, hid=hid, out=out, esz=lesz,
-                           bytes=gather_model_bytes(nnz, int(info.n_own), d_in, lesz, layer.mode == "gcn"),
+                           bytes=gather_model_bytes(nnz, int(info.n_own), d_in, lesz, layer.mode == "gcn", 2 if bf16 else 4),
                            flops=sum(2.0 * info.n_own * layer.dims[i] * layer.dims[i + 1] for i in range(len(ws)))))
 
     def step(events=None):
@@ -511,10 +514,14 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
         L0 = layers[0]
         ref = oracle.aggregate(w.row_ptr, w.col, L0["layer"].mode, x_local_np, lb=w.lb, ub=w.ub, x_halo=x_halo_np,
                                halo_gid=halo_gid, eps=L0["layer"].eps, rows=rows)
-        got = L0["agg"][torch.from_numpy(rows).to(dev)].cpu().numpy().astype(np.float64)
+        got = L0["agg"][torch.from_numpy(rows).to(dev)].float().cpu().numpy().astype(np.float64)
         err = np.abs(got - ref)
+        if L0["agg"].dtype == torch.bfloat16:      # rounded to bf16 on the way out: half a unit in the 8th bit
+            bound, what = 2.0 ** -8 * np.abs(ref) + 1e-30, "2^-8 |ref|"
+        else:
+            bound, what = 1e-6 + 1e-4 * np.abs(ref), "(1e-6 + 1e-4|ref|)"
         log(f"[bench] verify layer-0 aggregation on {rows.size} sampled rows: max abs err {err.max():.3e}, "
-            f"max err / (1e-6 + 1e-4|ref|) = {(err / (1e-6 + 1e-4 * np.abs(ref))).max():.3f}")
+            f"max err / {what} = {(err / bound).max():.3f}")
 
     cpu_baseline = None
     if cpu_budget_s > 0:

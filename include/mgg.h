@@ -172,6 +172,14 @@ mgg_status_t mgg_aggregate(const mgg_partition_t *p, mgg_agg_t mode, float eps, 
                            const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x,
                            float *out, int64_t ld_out, void *stream);
 
+/* mgg_aggregate with a choice of output type: out_dtype MGG_F32 is mgg_aggregate; MGG_BF16 rounds
+ * the fp32 sums to bf16 (nearest even) as they are written, out then being [n_own x dim] bf16.  A
+ * bf16 MFMA rounds its input the same way, so feeding it the bf16 rows gives the bits it would
+ * have computed from the fp32 rows, for half the bytes written and read back. */
+mgg_status_t mgg_aggregate_to(const mgg_partition_t *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
+                              const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x,
+                              mgg_dtype_t out_dtype, void *out, int64_t ld_out, void *stream);
+
 /* ---------------------------------------------------------------------------------------
  * mgg_update -- section 1 (Update = a fully-connected layer), section 7 (X W, ReLU, MLP):
  *     out = act(a . w + bias)        on MFMA, fp32 accumulation.
@@ -189,7 +197,7 @@ mgg_status_t mgg_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int6
 /* ---------------------------------------------------------------------------------------
  * mgg_update_mlp -- section 7, GIN: the Update is an MLP; two chained mgg_update calls,
  *     out = act2(act1(a . w1 + bias1) . w2 + bias2),      dims = {d_in, d_hidden, d_out}.
- * With bf16 weights, fp32 a, d_in 64 or 128, 33..128 hidden and output columns and
+ * With bf16 weights, d_in 64 or 128, 33..128 hidden and output columns and
  * elementwise activations both products run in ONE kernel and the hidden activations stay
  * in registers (rounded to bf16, as the two-call form keeps them).  Any other shape runs as
  * two launches through `hidden`, a DEVICE buffer [n_rows x d_hidden] (bf16 with bf16

@@ -27,7 +27,7 @@ _STATUS_NAME = ["OK", "INVALID_ARG", "BAD_GRAPH", "UNSUPPORTED", "ALLOC", "HIP"]
 
 EXPORTED_SYMBOLS = [
     "mgg_build_partition", "mgg_partition_info", "mgg_partition_export", "mgg_partition_destroy",
-    "mgg_aggregate", "mgg_update", "mgg_update_mlp", "mgg_layer_workspace_bytes", "mgg_layer_forward",
+    "mgg_aggregate", "mgg_aggregate_to", "mgg_update", "mgg_update_mlp", "mgg_layer_workspace_bytes", "mgg_layer_forward",
     "mgg_split_edge_balanced", "mgg_set_option", "mgg_get_option", "mgg_time_aggregate",
     "mgg_model_evaluate", "mgg_tuner_create", "mgg_tuner_next", "mgg_tuner_report", "mgg_tuner_result",
     "mgg_tuner_table", "mgg_tuner_destroy", "mgg_tune_aggregate",
@@ -112,6 +112,8 @@ def lib():
         L.mgg_partition_export.argtypes = [C.c_void_p, C.POINTER(PartitionArrays)]
         L.mgg_aggregate.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_int32,
                                     C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
+        L.mgg_aggregate_to.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_int32,
+                                       C.c_int64, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
         L.mgg_update.argtypes = [C.c_int64, C.c_int, C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p,
                                  C.c_void_p, C.c_int32, C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
         L.mgg_update_mlp.argtypes = [C.c_int64, C.c_int, C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_int, C.c_void_p,
@@ -274,14 +276,20 @@ def mgg_get_option(key: str) -> int:
 
 # ------------------------------------------------------------------------------- device calls
 def mgg_aggregate(part: Partition, mode: str, x_local, x_halo=None, *, eps: float = 0.0, out=None,
-                  dim: Optional[int] = None, stream=None):
-    """out[n_own x dim] (fp32) = Aggregate over N(v) U {v}; tensors are torch CUDA tensors."""
+                  dim: Optional[int] = None, stream=None, out_dtype=None):
+    """out[n_own x dim] = Aggregate over N(v) U {v}; fp32, or bf16 (mgg_aggregate_to) when `out` or
+    `out_dtype` says so; tensors are torch CUDA tensors."""
     import torch
     dim = int(x_local.shape[1]) if dim is None else dim
     if out is None:
-        out = torch.empty((int(part.info.n_own), dim), dtype=torch.float32, device=x_local.device)
-    _check(lib().mgg_aggregate(part.handle, _MODE[mode], eps, _torch_dtype_code(x_local), _dev_ptr(x_local),
-                               _dev_ptr(x_halo), dim, _ld(x_local), _dev_ptr(out), _ld(out), _stream(stream)))
+        out = torch.empty((int(part.info.n_own), dim), dtype=out_dtype or torch.float32, device=x_local.device)
+    if out.dtype == torch.float32:
+        _check(lib().mgg_aggregate(part.handle, _MODE[mode], eps, _torch_dtype_code(x_local), _dev_ptr(x_local),
+                                   _dev_ptr(x_halo), dim, _ld(x_local), _dev_ptr(out), _ld(out), _stream(stream)))
+    else:
+        _check(lib().mgg_aggregate_to(part.handle, _MODE[mode], eps, _torch_dtype_code(x_local), _dev_ptr(x_local),
+                                      _dev_ptr(x_halo), dim, _ld(x_local), _torch_dtype_code(out), _dev_ptr(out), _ld(out),
+                                      _stream(stream)))
     return out
 
 

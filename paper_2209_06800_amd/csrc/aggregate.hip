@@ -35,7 +35,8 @@ struct AggArgs {
     const int32_t *short_rows;
     const WorkItem *items;
     const void *x_local, *x_halo;
-    float *out, *scratch;
+    void *out;               // fp32, or bf16 when out_bf16 (rounded to nearest even)
+    float *scratch;
     int64_t ld_x, ld_out, scratch_ld;
     int32_t nvec;            // vectors of VEC elements per row (dim / VEC)
     int32_t slab_vecs;       // vectors per column slab; blockIdx.y selects the slab (= nvec: one slab)
@@ -43,6 +44,7 @@ struct AggArgs {
     int32_t ps;
     int32_t gcn;             // 1: symmetric normalisation, 0: plain sum
     float self_w;            // GIN: 1 + eps
+    int32_t out_bf16;
     int32_t out_vec_ok;      // out rows allow VEC-wide stores
     int32_t out_dim;         // columns of `out` that exist (<= nvec * VEC; the rest of the last vector is padding of the tables)
     int32_t phase;           // 0: local and remote lists in one launch; 1: local lists (+ self term) only;
@@ -101,6 +103,30 @@ __device__ __forceinline__ void store_vec(float *dst, const float (&v)[VEC], boo
     }
 }
 
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);       // round to nearest, ties to even
+    return u >> 16;
+}
+
+// bf16 output: the same VEC values, rounded, as one 2*VEC-byte store when the layout allows
+template <int VEC>
+__device__ __forceinline__ void store_vec_bf16(uint16_t *dst, const float (&v)[VEC], bool vec_ok)
+{
+    if (vec_ok && VEC >= 2) {
+        uint32_t pk[VEC >= 2 ? VEC / 2 : 1];
+#pragma unroll
+        for (int e = 0; e < VEC / 2; ++e) pk[e] = f32_to_bf16_bits(v[2 * e]) | (f32_to_bf16_bits(v[2 * e + 1]) << 16);
+        if constexpr (VEC == 8) *reinterpret_cast<uint4 *>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        else if constexpr (VEC == 4) *reinterpret_cast<uint2 *>(dst) = make_uint2(pk[0], pk[1]);
+        else if constexpr (VEC == 2) *reinterpret_cast<uint32_t *>(dst) = pk[0];
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) dst[e] = static_cast<uint16_t>(f32_to_bf16_bits(v[e]));
+    }
+}
+
 // ---- one kernel configuration --------------------------------------------------------------
 template <bool BF16_, int VEC_, int LPR_, int CH_>
 struct Cfg {
@@ -129,7 +155,8 @@ template <class K>
 __device__ __forceinline__ void write_final(const AggArgs &a, const Acc<K> &acc, int32_t row, int lis, int vend)
 {
     const typename K::elem *xs = static_cast<const typename K::elem *>(a.x_local) + static_cast<int64_t>(row) * a.ld_x;
-    float *o = a.out + static_cast<int64_t>(row) * a.ld_out;
+    float *o = static_cast<float *>(a.out) + static_cast<int64_t>(row) * a.ld_out;             // fp32 output
+    uint16_t *ob = static_cast<uint16_t *>(a.out) + static_cast<int64_t>(row) * a.ld_out;     // bf16 output
     const float dv = a.gcn ? a.dinv_own[row] : 1.f;
     const float ws = a.gcn ? dv : a.self_w;     // GCN: dv * (sum + dv * x_v) = sum_u x_u/sqrt(du dv) + x_v/dv^2
 #pragma unroll
@@ -157,7 +184,15 @@ __device__ __forceinline__ void write_final(const AggArgs &a, const Acc<K> &acc,
                 }
             }
             const int col0 = vi * K::VEC;
-            if (col0 + K::VEC <= a.out_dim) {
+            if (a.out_bf16) {                   // (never combined with phase 2, which reads `out` back)
+                if (col0 + K::VEC <= a.out_dim) {
+                    store_vec_bf16<K::VEC>(ob + col0, r, a.out_vec_ok);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < K::VEC; ++e)
+                        if (col0 + e < a.out_dim) ob[col0 + e] = static_cast<uint16_t>(f32_to_bf16_bits(r[e]));
+                }
+            } else if (col0 + K::VEC <= a.out_dim) {
                 store_vec<K::VEC>(o + col0, r, a.out_vec_ok);
             } else {                            // last vector reaches into the padding: store what exists
 #pragma unroll
@@ -410,7 +445,7 @@ __global__ __launch_bounds__(kWave * kMaxWpb) void aggregate_kernel(const AggArg
 template <bool BF16>
 __global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_rows, int32_t n_split, int32_t dim, const float *scratch,
                                                        int64_t scratch_ld, const void *x_local, int64_t ld_x,
-                                                       const float *dinv_own, int32_t gcn, float self_w, float *out,
+                                                       const float *dinv_own, int32_t gcn, float self_w, void *out_v, int32_t out_bf16,
                                                        int64_t ld_out, int32_t out_vec_ok, int32_t phase, const float *bias, int32_t relu)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -437,7 +472,8 @@ __global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_row
             sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
         }
         const float total[4] = {sum.x, sum.y, sum.z, sum.w};
-        float *o = out + static_cast<int64_t>(sr.row) * ld_out + k;
+        float *o = static_cast<float *>(out_v) + static_cast<int64_t>(sr.row) * ld_out + k;
+        uint16_t *ob = static_cast<uint16_t *>(out_v) + static_cast<int64_t>(sr.row) * ld_out + k;
         float r[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -455,7 +491,16 @@ __global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_row
                 }
             }
         }
-        if (out_vec_ok && k + 3 < dim) {
+        if (out_bf16) {
+            if (out_vec_ok && k + 3 < dim) {
+                *reinterpret_cast<uint2 *>(ob) = make_uint2(f32_to_bf16_bits(r[0]) | (f32_to_bf16_bits(r[1]) << 16),
+                                                            f32_to_bf16_bits(r[2]) | (f32_to_bf16_bits(r[3]) << 16));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (k + e < dim) ob[e] = static_cast<uint16_t>(f32_to_bf16_bits(r[e]));
+            }
+        } else if (out_vec_ok && k + 3 < dim) {
             *reinterpret_cast<float4 *>(o) = make_float4(r[0], r[1], r[2], r[3]);
         } else {
 #pragma unroll
@@ -497,8 +542,9 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 }  // namespace
 
 mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
-                              const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x, float *out,
-                              int64_t ld_out, hipStream_t stream, const float *bias, mgg_act_t act, int32_t out_dim)
+                              const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x, void *out,
+                              int64_t ld_out, hipStream_t stream, const float *bias, mgg_act_t act, int32_t out_dim,
+                              mgg_dtype_t out_dtype)
 {
     const bool bf16 = x_dtype == MGG_BF16;
     const size_t esz = bf16 ? 2 : 4;
@@ -577,12 +623,17 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
     a.bias = bias;
     a.out_dim = out_dim;
     a.relu = act == MGG_ACT_RELU;
-    const size_t out_bytes = (vec >= 4 ? 4 : vec) * sizeof(float);
-    a.out_vec_ok = (ld_out % (vec >= 4 ? 4 : vec) == 0) && aligned(out, out_bytes);
+    a.out_bf16 = out_dtype == MGG_BF16;
+    if (a.out_bf16) {           // one store of 2 * vec bytes per vector
+        a.out_vec_ok = (ld_out % vec == 0) && aligned(out, static_cast<size_t>(vec) * 2);
+    } else {                    // 16-byte stores at most (two per 8-element vector)
+        const size_t out_bytes = (vec >= 4 ? 4 : vec) * sizeof(float);
+        a.out_vec_ok = (ld_out % (vec >= 4 ? 4 : vec) == 0) && aligned(out, out_bytes);
+    }
 
     // one launch for both neighbour lists (the default), or -- as the ablation of interleaving --
     // the local lists first and the remote lists in a second launch that adds to the result
-    const bool two_phases = option_split_phases() != 0 && !p->halo_gid.empty();
+    const bool two_phases = option_split_phases() != 0 && !p->halo_gid.empty() && !a.out_bf16;   // phase 2 reads `out` back
     for (int phase = two_phases ? 1 : 0; phase <= (two_phases ? 2 : 0); ++phase) {
         a.phase = phase;
         const int npw = 64 / lpr;
@@ -607,13 +658,13 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
         const int32_t n_split = static_cast<int32_t>(p->split_rows.size());
         if (n_split > 0) {
             const dim3 fgrid(static_cast<unsigned>((n_split + kWavesPerBlock - 1) / kWavesPerBlock));
-            const int32_t fix_vec_ok = (ld_out % 4 == 0) && aligned(out, 16);
+            const int32_t fix_vec_ok = (ld_out % 4 == 0) && aligned(out, a.out_bf16 ? 8 : 16);
             if (bf16)
                 hipLaunchKernelGGL(fixup_kernel<true>, fgrid, dim3(kBlock), 0, stream, p->d.split_rows, n_split, out_dim, p->d.scratch,
-                                   p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out, fix_vec_ok, a.phase, bias, a.relu);
+                                   p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, a.out_bf16, ld_out, fix_vec_ok, a.phase, bias, a.relu);
             else
                 hipLaunchKernelGGL(fixup_kernel<false>, fgrid, dim3(kBlock), 0, stream, p->d.split_rows, n_split, out_dim, p->d.scratch,
-                                   p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, ld_out, fix_vec_ok, a.phase, bias, a.relu);
+                                   p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, a.out_bf16, ld_out, fix_vec_ok, a.phase, bias, a.relu);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return hip_fail(e, "fix-up kernel launch");
         }

@@ -20,7 +20,8 @@ static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; 
 static inline bool dtype_ok(mgg_dtype_t t) { return t == MGG_F32 || t == MGG_BF16; }
 
 static mgg_status_t check_aggregate(const mgg_partition *p, mgg_agg_t mode, mgg_dtype_t x_dtype, const void *x_local,
-                                    const void *x_halo, int32_t dim, int64_t ld_x, const float *out, int64_t ld_out)
+                                    const void *x_halo, int32_t dim, int64_t ld_x, const void *out, int64_t ld_out,
+                                    mgg_dtype_t out_dtype = MGG_F32)
 {
     if (!p) return fail(MGG_ERR_INVALID_ARG, "partition is NULL");
     if (p->device < 0) return fail(MGG_ERR_INVALID_ARG, "partition was built host-only");
@@ -30,7 +31,9 @@ static mgg_status_t check_aggregate(const mgg_partition *p, mgg_agg_t mode, mgg_
     if (p->n_own > 0 && (!x_local || !out)) return fail(MGG_ERR_INVALID_ARG, "x_local or out is NULL");
     if (!p->halo_gid.empty() && !x_halo) return fail(MGG_ERR_INVALID_ARG, "x_halo is NULL but the partition has %zu halo rows", p->halo_gid.size());
     const size_t esz = x_dtype == MGG_BF16 ? 2 : 4;
-    if (reinterpret_cast<uintptr_t>(x_local) % esz || reinterpret_cast<uintptr_t>(x_halo) % esz || reinterpret_cast<uintptr_t>(out) % 4)
+    if (!dtype_ok(out_dtype)) return fail(MGG_ERR_INVALID_ARG, "unknown output dtype");
+    if (reinterpret_cast<uintptr_t>(x_local) % esz || reinterpret_cast<uintptr_t>(x_halo) % esz ||
+        reinterpret_cast<uintptr_t>(out) % (out_dtype == MGG_BF16 ? 2 : 4))
         return fail(MGG_ERR_INVALID_ARG, "pointer not aligned to its element size");
     int dev = -1;
     MGG_HIP_TRY(hipGetDevice(&dev));
@@ -104,6 +107,17 @@ mgg_status_t mgg_aggregate(const mgg_partition_t *p, mgg_agg_t mode, float eps, 
     if (s != MGG_OK) return s;
     if (p->n_own == 0) return MGG_OK;
     return launch_aggregate(p, mode, eps, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out, static_cast<hipStream_t>(stream));
+}
+
+mgg_status_t mgg_aggregate_to(const mgg_partition_t *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype, const void *x_local,
+                              const void *x_halo, int32_t dim, int64_t ld_x, mgg_dtype_t out_dtype, void *out, int64_t ld_out,
+                              void *stream)
+{
+    mgg_status_t s = check_aggregate(p, mode, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out, out_dtype);
+    if (s != MGG_OK) return s;
+    if (p->n_own == 0) return MGG_OK;
+    return launch_aggregate(p, mode, eps, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out, static_cast<hipStream_t>(stream), nullptr,
+                            MGG_ACT_NONE, 0, out_dtype);
 }
 
 mgg_status_t mgg_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in,
@@ -182,27 +196,30 @@ mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t 
                              out_dtype, out, ld_out, st);
     }
 
-    float *agg = static_cast<float *>(workspace);
+    // With bf16 weights the rows are rounded to bf16 on the way into the MFMA anyway; rounding them on the
+    // way out of the aggregation gives the same bits and halves what is written and read back.
+    void *agg = workspace;
+    const mgg_dtype_t agg_dtype = layer->w_dtype == MGG_BF16 ? MGG_BF16 : MGG_F32;
     void *hid = static_cast<char *>(workspace) + pl.agg_bytes;
     // validate everything before the first launch so that an error leaves no partial output
-    s = check_aggregate(p, layer->mode, x_dtype, x_local, x_halo, d0, ld_x, agg, pl.ld_agg);
+    s = check_aggregate(p, layer->mode, x_dtype, x_local, x_halo, d0, ld_x, agg, pl.ld_agg, agg_dtype);
     if (s != MGG_OK) return s;
     if (layer->n_linear == 1)
-        s = check_update(p->n_own, MGG_F32, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], d1, layer->act[0], out_dtype, out, ld_out);
+        s = check_update(p->n_own, agg_dtype, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], d1, layer->act[0], out_dtype, out, ld_out);
     else {
-        s = check_update(p->n_own, MGG_F32, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], d1, layer->act[0], pl.hid_dtype, hid, pl.ld_hid);
+        s = check_update(p->n_own, agg_dtype, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], d1, layer->act[0], pl.hid_dtype, hid, pl.ld_hid);
         if (s == MGG_OK)
             s = check_update(p->n_own, pl.hid_dtype, hid, pl.ld_hid, d1, layer->w_dtype, layer->w[1], d2, layer->act[1], out_dtype, out, ld_out);
     }
     if (s != MGG_OK) return s;
     if (p->n_own == 0) return MGG_OK;
 
-    s = launch_aggregate(p, layer->mode, layer->eps, x_dtype, x_local, x_halo, d0, ld_x, agg, pl.ld_agg, st);
+    s = launch_aggregate(p, layer->mode, layer->eps, x_dtype, x_local, x_halo, d0, ld_x, agg, pl.ld_agg, st, nullptr, MGG_ACT_NONE, 0, agg_dtype);
     if (s != MGG_OK) return s;
     if (layer->n_linear == 1)
-        return launch_update(p->n_own, MGG_F32, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], layer->bias[0], d1,
+        return launch_update(p->n_own, agg_dtype, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], layer->bias[0], d1,
                              layer->act[0], out_dtype, out, ld_out, st);
-    return launch_update_mlp(p->n_own, MGG_F32, agg, pl.ld_agg, layer->dims, layer->w_dtype, layer->w[0], layer->bias[0], layer->act[0],
+    return launch_update_mlp(p->n_own, agg_dtype, agg, pl.ld_agg, layer->dims, layer->w_dtype, layer->w[0], layer->bias[0], layer->act[0],
                              layer->w[1], layer->bias[1], layer->act[1], hid, pl.ld_hid, out_dtype, out, ld_out, st);
 }
 

@@ -98,10 +98,11 @@ int32_t option_update_stream();
 // kernels (aggregate.hip / update.hip)
 mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
                               const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x,
-                              float *out, int64_t ld_out, hipStream_t stream, const float *bias = nullptr,
-                              mgg_act_t act = MGG_ACT_NONE, int32_t out_dim = 0);
+                              void *out, int64_t ld_out, hipStream_t stream, const float *bias = nullptr,
+                              mgg_act_t act = MGG_ACT_NONE, int32_t out_dim = 0, mgg_dtype_t out_dtype = MGG_F32);
 // bias / act: optional epilogue of the final value.  out_dim (0 = dim): columns of `out` that exist
-// when the tables carry padding columns beyond them (dim counts the padded width).
+// when the tables carry padding columns beyond them (dim counts the padded width).  out_dtype BF16: the
+// rows are rounded to bf16 (nearest even) on the way out -- what the bf16 MFMA would do on the way in.
 mgg_status_t launch_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in,
                            mgg_dtype_t w_dtype, const void *w, const float *bias, int32_t d_out,
                            mgg_act_t act, mgg_dtype_t out_dtype, void *out, int64_t ld_out,

@@ -617,12 +617,12 @@ mgg_status_t launch_update_mlp(int64_t n_rows, mgg_dtype_t a_dtype, const void *
                                hipStream_t stream)
 {
     if (n_rows == 0) return MGG_OK;
-    if (w_dtype == MGG_BF16 && a_dtype == MGG_F32 && option_update_stream() != 0) {
+    if (w_dtype == MGG_BF16 && option_update_stream() != 0) {
         int dev = 0, cus = 256;
         if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         hipError_t e = hipSuccess;
-        if (launch_mlp_stream(n_rows, static_cast<const float *>(a), ld_a, dims[0], w1, b1, act1, dims[1], w2, b2, act2, dims[2], out_dtype,
-                              out, ld_out, cus, stream, &e)) {
+        if (launch_mlp_stream(n_rows, a_dtype, a, ld_a, dims[0], w1, b1, act1, dims[1], w2, b2, act2, dims[2], out_dtype, out, ld_out, cus,
+                              stream, &e)) {
             if (e != hipSuccess) return hip_fail(e, "MLP kernel launch");
             return MGG_OK;
         }

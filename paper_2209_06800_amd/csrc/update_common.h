@@ -210,8 +210,8 @@ bool launch_update_stream(const upd::UpdArgs &p, bool w_bf16, bool a_bf16, int c
 
 // Two linears with bf16 weights in one kernel, hidden tile kept in registers (update_stream.hip);
 // returns false when the shape is not covered and nothing was launched.
-bool launch_mlp_stream(int64_t n_rows, const float *a, int64_t ld_a, int32_t d_in, const void *w1, const float *b1, mgg_act_t act1,
-                       int32_t d_hid, const void *w2, const float *b2, mgg_act_t act2, int32_t d_out, mgg_dtype_t out_dtype, void *out,
-                       int64_t ld_out, int cus, hipStream_t stream, hipError_t *err);
+bool launch_mlp_stream(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in, const void *w1, const float *b1,
+                       mgg_act_t act1, int32_t d_hid, const void *w2, const float *b2, mgg_act_t act2, int32_t d_out,
+                       mgg_dtype_t out_dtype, void *out, int64_t ld_out, int cus, hipStream_t stream, hipError_t *err);
 
 }  // namespace mgg

@@ -320,7 +320,7 @@ void update_f32_stream_kernel(const UpdArgs p)
 }
 
 // ---- two linears in one kernel (GIN's MLP, section 7) ------------------------------------------
-// out = act2(act1(A W1 + b1) W2 + b2) with bf16 weights, fp32 A (the aggregation result), a hidden
+// out = act2(act1(A W1 + b1) W2 + b2) with bf16 weights, A the aggregation result (fp32 or bf16), a hidden
 // width of at most 128.  The hidden tile never leaves the registers: the accumulators of the first
 // product (register r of lane (m, h), tile t: row m, hidden column 32 t + 8 (r/4) + 4 h + r%4) get bias
 // and ReLU, are rounded to bf16 -- as the hidden activations of the two-launch path are -- and eight
@@ -331,7 +331,7 @@ constexpr int kMlpWaves = 8;
 constexpr int kMlpThreads = kWave * kMlpWaves;
 
 struct MlpArgs {
-    const float *a;
+    const void *a;           // fp32 or bf16
     const uint16_t *w1, *w2;
     const float *b1, *b2;
     void *out;
@@ -340,7 +340,7 @@ struct MlpArgs {
     int32_t relu1, relu2, out_vec_ok;
 };
 
-template <int NS1, int NT2, bool OUT_BF16>
+template <int NS1, int NT2, bool A_BF16, bool OUT_BF16>
 __global__ __launch_bounds__(kMlpThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void mlp_bf16_stream_kernel(const MlpArgs m)
 {
@@ -380,10 +380,10 @@ void mlp_bf16_stream_kernel(const MlpArgs m)
     if (tile >= n_tiles) return;
     int64_t itile = tile;
     int is = 0;
-    Raw<false> q;
+    Raw<A_BF16> q;
     auto issue = [&]() {
-        Raw<false> r;
-        load_slab<false>(pa, itile, is, lane, r);
+        Raw<A_BF16> r;
+        load_slab<A_BF16>(pa, itile, is, lane, r);
         if (++is == NS1) { is = 0; itile += stride; }
         return r;
     };
@@ -397,7 +397,7 @@ void mlp_bf16_stream_kernel(const MlpArgs m)
             for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 #pragma unroll
         for (int s = 0; s < NS1; ++s) {
-            stage_slab<false, LDA>(q, abuf, lane);
+            stage_slab<A_BF16, LDA>(q, abuf, lane);
             q = issue();
             wave_sync_lds();
 #pragma unroll
@@ -450,22 +450,21 @@ void mlp_bf16_stream_kernel(const MlpArgs m)
 }
 
 template <int NS1, int NT2>
-hipError_t launch_mlp(const MlpArgs &m, bool out_bf16, int cus, hipStream_t s)
+hipError_t launch_mlp(const MlpArgs &m, bool a_bf16, bool out_bf16, int cus, hipStream_t s)
 {
     constexpr int W1_BYTES = (128 * (NS1 * 64 + 8) * 2 + 15) / 16 * 16, W2_BYTES = (NT2 * 32 * 136 * 2 + 15) / 16 * 16;
     const int wave_bytes = out_bf16 ? wave_lds_bytes<NT2, true>(32 * 72 * 2) : wave_lds_bytes<NT2, false>(32 * 72 * 2);
     const size_t lds = static_cast<size_t>(W1_BYTES) + W2_BYTES + kMlpWaves * static_cast<size_t>(wave_bytes);
     const int64_t want = ((m.n_rows + 31) / 32 + kMlpWaves - 1) / kMlpWaves;
     const int blocks = static_cast<int>(want < cus ? want : cus);      // the LDS of a CU holds one workgroup
-    static bool raised[2] = {false, false};
-    if (out_bf16) {
-        if (!raised[1]) { (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&mlp_bf16_stream_kernel<NS1, NT2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)); raised[1] = true; }
-        hipLaunchKernelGGL((mlp_bf16_stream_kernel<NS1, NT2, true>), dim3(blocks), dim3(kMlpThreads), lds, s, m);
-    } else {
-        if (!raised[0]) { (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&mlp_bf16_stream_kernel<NS1, NT2, false>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)); raised[0] = true; }
-        hipLaunchKernelGGL((mlp_bf16_stream_kernel<NS1, NT2, false>), dim3(blocks), dim3(kMlpThreads), lds, s, m);
-    }
-    return hipGetLastError();
+    auto go = [&](auto kernel) {
+        // more than 64 KB of dynamic LDS: ask for it (cheap, so done at every launch rather than remembered)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kMlpThreads), lds, s, m);
+        return hipGetLastError();
+    };
+    if (a_bf16) return out_bf16 ? go(mlp_bf16_stream_kernel<NS1, NT2, true, true>) : go(mlp_bf16_stream_kernel<NS1, NT2, true, false>);
+    return out_bf16 ? go(mlp_bf16_stream_kernel<NS1, NT2, false, true>) : go(mlp_bf16_stream_kernel<NS1, NT2, false, false>);
 }
 
 template <int NT, int NS>
@@ -507,13 +506,14 @@ hipError_t launch_f32(const UpdArgs &p, int cus, hipStream_t s)
 
 }  // namespace
 
-bool launch_mlp_stream(int64_t n_rows, const float *a, int64_t ld_a, int32_t d_in, const void *w1, const float *b1, mgg_act_t act1,
-                       int32_t d_hid, const void *w2, const float *b2, mgg_act_t act2, int32_t d_out, mgg_dtype_t out_dtype, void *out,
-                       int64_t ld_out, int cus, hipStream_t stream, hipError_t *err)
+bool launch_mlp_stream(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in, const void *w1, const float *b1,
+                       mgg_act_t act1, int32_t d_hid, const void *w2, const float *b2, mgg_act_t act2, int32_t d_out,
+                       mgg_dtype_t out_dtype, void *out, int64_t ld_out, int cus, hipStream_t stream, hipError_t *err)
 {
-    // covered: fp32 A whose rows allow 16-byte loads, d_in = 64 or 128, 33..128 hidden and output columns,
-    // elementwise activations
-    if ((reinterpret_cast<uintptr_t>(a) & 15u) || ld_a % 4 || (d_in != 64 && d_in != 128)) return false;
+    // covered: A (fp32 or bf16) whose rows allow 16-byte loads, d_in = 64 or 128, 33..128 hidden and output
+    // columns, elementwise activations
+    const bool ab = a_dtype == MGG_BF16;
+    if ((reinterpret_cast<uintptr_t>(a) & 15u) || ld_a % (ab ? 8 : 4) || (d_in != 64 && d_in != 128)) return false;
     if (d_hid <= 32 || d_hid > 128 || d_out <= 32 || d_out > 128) return false;
     if ((act1 != MGG_ACT_NONE && act1 != MGG_ACT_RELU) || (act2 != MGG_ACT_NONE && act2 != MGG_ACT_RELU)) return false;
     MlpArgs m{};
@@ -523,8 +523,8 @@ bool launch_mlp_stream(int64_t n_rows, const float *a, int64_t ld_a, int32_t d_i
     const bool ob = out_dtype == MGG_BF16;
     m.out_vec_ok = (ld_out % 4 == 0) && (reinterpret_cast<uintptr_t>(out) % (ob ? 8 : 16) == 0);
     const int nt2 = d_out > 64 ? 4 : 2;
-    if (d_in == 64) *err = nt2 == 4 ? launch_mlp<1, 4>(m, ob, cus, stream) : launch_mlp<1, 2>(m, ob, cus, stream);
-    else *err = nt2 == 4 ? launch_mlp<2, 4>(m, ob, cus, stream) : launch_mlp<2, 2>(m, ob, cus, stream);
+    if (d_in == 64) *err = nt2 == 4 ? launch_mlp<1, 4>(m, ab, ob, cus, stream) : launch_mlp<1, 2>(m, ab, ob, cus, stream);
+    else *err = nt2 == 4 ? launch_mlp<2, 4>(m, ab, ob, cus, stream) : launch_mlp<2, 2>(m, ab, ob, cus, stream);
     return true;
 }
 

@@ -272,6 +272,32 @@ def test_local_and_remote_in_two_launches_give_the_same_answer(dim, bf16, mode):
         binding.mgg_set_option("split_phases", 0)
 
 
+@pytest.mark.parametrize("dim,bf16_in,mode,build", [(64, False, "gcn", {}), (128, True, "gin", {}), (47, False, "gcn", dict(ps=7, dist=2)),
+                                                     (602, False, "gcn", dict(xcd_min_deg=30)), (130, True, "gin", dict(short_max=-1)),
+                                                     (8, True, "gcn", dict(hot_phases=2))])
+def test_aggregate_bf16_output_is_the_rounded_fp32_output(dim, bf16_in, mode, build):
+    """mgg_aggregate_to with bf16 output rounds the same fp32 sums (nearest even) as they are written:
+    bit for bit what rounding the fp32 output gives, so a bf16 MFMA fed either way sees the same input."""
+    row_ptr, col, rng = small_rmat(seed=31)
+    n = row_ptr.size - 1
+    bounds = inputs.equal_node_bounds(n, 3)
+    x = rng.standard_normal((n, dim)).astype(np.float32)
+    if bf16_in:
+        x = inputs.to_bf16_bits(x)
+    for p in range(3):
+        part = binding.mgg_build_partition(row_ptr, col, 3, p, bounds, **build)
+        hg = part.export()["halo_gid"]
+        xl, xh = to_dev(x[bounds[p]:bounds[p + 1]]), (to_dev(x[hg]) if hg.size else None)
+        f32 = binding.mgg_aggregate(part, mode, xl, xh, eps=0.5)
+        buf = torch.full((int(part.info.n_own), dim + 5), float("nan"), dtype=torch.bfloat16, device=DEV)
+        b16 = binding.mgg_aggregate(part, mode, xl, xh, eps=0.5, out=buf[:, :dim])
+        aligned = binding.mgg_aggregate(part, mode, xl, xh, eps=0.5, out_dtype=torch.bfloat16)
+        torch.cuda.synchronize()
+        assert torch.isnan(buf[:, dim:]).all()
+        assert torch.equal(b16, f32.to(torch.bfloat16)) and torch.equal(aligned, b16)
+        part.destroy()
+
+
 # ----------------------------------------------------------------------------- update
 def update_bound(a64, w64, k, bf16):
     s = np.abs(a64) @ np.abs(w64)
@@ -414,8 +440,10 @@ def test_update_mlp(n_rows, dims, acts, with_bias, out_bf16):
     covered = dims[0] in (64, 128) and 32 < dims[1] <= 128 and 32 < dims[2] <= 128
     if covered:                                           # the one-kernel form needs no hidden buffer
         again = binding.mgg_update_mlp(to_dev(a), to_dev(w[0]), to_dev(w[1]), acts, d_b, out_dtype=odt)
+        # input already rounded to bf16: the bits the kernel makes of the fp32 input itself
+        from_bf16 = binding.mgg_update_mlp(to_dev(a).to(torch.bfloat16), to_dev(w[0]), to_dev(w[1]), acts, d_b, out_dtype=odt)
         torch.cuda.synchronize()
-        assert torch.equal(again, got)
+        assert torch.equal(again, got) and torch.equal(from_bf16, got)
     else:
         with pytest.raises(binding.MggError):
             binding.mgg_update_mlp(to_dev(a), to_dev(w[0]), to_dev(w[1]), acts, d_b, out_dtype=odt)
