@@ -573,12 +573,18 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
         const int64_t vec_bytes = static_cast<int64_t>(vec) * static_cast<int64_t>(esz);
         int64_t slab_bytes = 0;
         if (opt == 0) {
-            // automatic: measured on MI355X, 512-byte slabs pay (1.1-1.3x) when rows are at least
-            // two slabs wide and one XCD's share of the table rows, at slab width, stays within a
-            // few times its 4 MB L2; narrower slabs or larger tables lose to the extra passes
+            // automatic: measured on MI355X, slabs pay (1.1-1.5x) when rows are at least 1 KB wide and one
+            // XCD's share of the table rows, at slab width, stays within a few times its 4 MB L2: 512-byte
+            // slabs when that share is at most 8 MB, else 256-byte slabs if those get it there (the
+            // 233 k x 2.4 KB table of the configs: 18.7 ms against 20.5 with 512 and 20.4 with 128), else
+            // 512-byte slabs up to 16 MB; narrower slabs or larger tables lose to the extra passes
             const int64_t table_rows = p->n_own + static_cast<int64_t>(p->halo_gid.size());
             const int64_t class_rows = (p->xcd_min_deg > 0 ? table_rows / kXcd : table_rows) + 1;
-            if (static_cast<int64_t>(dim) * static_cast<int64_t>(esz) >= 1024 && class_rows * 512 <= (16 << 20)) slab_bytes = 512;
+            if (static_cast<int64_t>(dim) * static_cast<int64_t>(esz) >= 1024) {
+                if (class_rows * 512 <= (8 << 20)) slab_bytes = 512;
+                else if (class_rows * 256 <= (8 << 20)) slab_bytes = 256;
+                else if (class_rows * 512 <= (16 << 20)) slab_bytes = 512;
+            }
         } else if (opt >= 64) {
             slab_bytes = opt;
         }
