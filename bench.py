@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 MEASURED_TRAFFIC_BYTES = {
     "cfg2_rmat20_gcn64_p4": 1896712204,          # profiles/aggregate_cfg2_rmat20_gcn64.md
     "cfg3_rmat22_gin128_bf16_p8": 4361605664,    # profiles/aggregate_cfg3_rmat22_gin128_bf16.md
-    "cfg4_powerlaw233k_gcn602": 145389948293,    # profiles/aggregate_cfg4_powerlaw233k_gcn602.md
+    "cfg4_powerlaw233k_gcn602": 105485911303,    # profiles/aggregate_cfg4_powerlaw233k_gcn602.md
     "cfg5_rmat2.4M_gcn2layer_p8": 34754240991,   # profiles/aggregate_cfg5_rmat2.4M_gcn_dim100_dim256.md (layer 1, dim 256)
 }
 
