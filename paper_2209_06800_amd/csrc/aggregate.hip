@@ -23,6 +23,9 @@ namespace mgg {
 
 namespace {
 
+#ifndef MGG_AGG_INFLIGHT
+#define MGG_AGG_INFLIGHT 8          // 16-byte loads a lane keeps in flight
+#endif
 constexpr int kWave = 64;
 constexpr int kWavesPerBlock = 4;                   // fix-up kernel, and the LDS stage of the staged variant
 constexpr int kBlock = kWave * kWavesPerBlock;
@@ -133,7 +136,7 @@ struct Cfg {
     static constexpr bool BF16 = BF16_;
     static constexpr int VEC = VEC_, LPR = LPR_, CH = CH_;
     static constexpr int NPW = kWave / LPR;                 // neighbour rows per load instruction
-    static constexpr int U = (8 / CH) > 0 ? (8 / CH) : 1;   // neighbour rows in flight per lane
+    static constexpr int U = (MGG_AGG_INFLIGHT / CH) > 0 ? (MGG_AGG_INFLIGHT / CH) : 1;   // neighbour rows in flight per lane
     using elem = typename std::conditional<BF16, uint16_t, float>::type;
     using raw = typename Raw<BF16, VEC>::type;
 };
