@@ -105,28 +105,17 @@ static void copy_out(const std::vector<T> &v, T *dst)
 }
 
 
-}  // namespace mgg
-
-using namespace mgg;
-
-extern "C" {
-
-const char *mgg_last_error(void) { return mgg::last_error(); }
-const char *mgg_version(void) { return "mgg-mi355x 0.1 (gfx950)"; }
-
-mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, const int32_t *col_idx,
-                                 int32_t num_parts, int32_t part_id, const int64_t *bounds,
-                                 const mgg_build_opts_t *opts, mgg_partition_t **out)
-{
-    if (!out) return fail(MGG_ERR_INVALID_ARG, "out is NULL");
-    *out = nullptr;
-    if (num_nodes < 0 || !row_ptr) return fail(MGG_ERR_INVALID_ARG, "num_nodes < 0 or row_ptr is NULL");
-    if (num_nodes > INT32_MAX - 1) return fail(MGG_ERR_UNSUPPORTED, "more than 2^31-2 nodes");
-    if (num_parts < 1 || part_id < 0 || part_id >= num_parts)
-        return fail(MGG_ERR_INVALID_ARG, "part_id %d outside [0, %d)", part_id, num_parts);
+// The knobs of a build with the defaults filled in.
+struct Knobs {
     int32_t ps = 64, dist = 8, short_max = 16, host_only = 0, xcd_min_deg = kDefaultXcdMinDeg, wpb = kDefaultWpb;
     int32_t hot_rows = 0, hot_phases = kDefaultHotPhases, min_piece = kDefaultMinPiece, hot_min_count = kDefaultHotMinCount;
+};
+
+static mgg_status_t parse_opts(const mgg_build_opts_t *opts, Knobs *k)
+{
+    int32_t &ps = k->ps, &dist = k->dist, &short_max = k->short_max, &host_only = k->host_only, &xcd_min_deg = k->xcd_min_deg, &wpb = k->wpb;
     int32_t hot_row_bytes = 256;
+    int32_t &hot_rows = k->hot_rows, &hot_phases = k->hot_phases, &min_piece = k->min_piece, &hot_min_count = k->hot_min_count;
     if (opts) {
         if (opts->hot_row_bytes) hot_row_bytes = opts->hot_row_bytes;
         if (opts->hot_rows) hot_rows = opts->hot_rows;
@@ -154,6 +143,208 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
     if (hot_phases > kMaxHotPhases) return fail(MGG_ERR_INVALID_ARG, "hot_phases %d above %d", hot_phases, kMaxHotPhases);
     if (min_piece < 1) return fail(MGG_ERR_INVALID_ARG, "min_piece %d below 1", min_piece);
     if (hot_min_count < 1) return fail(MGG_ERR_INVALID_ARG, "hot_min_count %d below 1", hot_min_count);
+    return MGG_OK;
+}
+
+// Source classes, work items and the short-row bin of a partition whose two CSRs are in place
+// (may throw std::bad_alloc).
+static void build_schedule(mgg_partition *p, const Knobs &k)
+{
+    const int64_t n_own = p->n_own, num_halo = static_cast<int64_t>(p->halo_gid.size());
+    const int32_t ps = k.ps, dist = k.dist, short_max = k.short_max, xcd_min_deg = k.xcd_min_deg, wpb = k.wpb;
+    const int32_t hot_rows = k.hot_rows, min_piece = k.min_piece, hot_min_count = k.hot_min_count;
+    int32_t hot_phases = k.hot_phases;
+    p->ps = ps; p->dist = dist; p->short_max = short_max; p->xcd_min_deg = xcd_min_deg; p->wpb = wpb;
+    p->hot_rows = hot_rows; p->hot_phases = hot_phases; p->min_piece = min_piece; p->hot_min_count = hot_min_count;
+
+    // ---- source classes -------------------------------------------------------------
+    // Every row of the two embedding tables gets a class.  hot_phases < 0: a hash of its index, 8
+    // classes, one per XCD, no cold class.  With hot_phases >= 1 (0 chooses between the two) the class is
+    // either (phase, XCD) -- "hot" -- or cold, and hot classes are filled in order of popularity (how many owned rows gather the
+    // table row): the 8*hot_rows most gathered rows form phase 0, dealt round-robin to the
+    // 8 XCDs, the next 8*hot_rows phase 1, and so on.  An XCD works through its phases in
+    // order, so at any time its L2 only has to hold hot_rows table rows, all of which are
+    // gathered many times.
+    const bool use_classes = xcd_min_deg > 0;
+    const int64_t n_tab = n_own + num_halo;                  // local rows first, then halo slots
+    int n_phase = 0;
+    if (use_classes) {
+        p->src_class.assign(static_cast<size_t>(n_tab), kColdClass);
+        std::vector<int32_t> order;                          // table rows, most gathered first
+        std::vector<int32_t> cnt;
+        const int64_t per_phase = static_cast<int64_t>(kXcd) * hot_rows;
+        if (hot_phases >= 0 && n_tab > 0) {
+            cnt.assign(static_cast<size_t>(n_tab), 0);
+            for (int32_t u : p->local_col) ++cnt[u];
+            for (int32_t u : p->remote_col) ++cnt[n_own + u];
+            // counting sort by gather count (ties: lower index first)
+            const int32_t max_cnt = *std::max_element(cnt.begin(), cnt.end());
+            std::vector<int64_t> start(static_cast<size_t>(max_cnt) + 2, 0);
+            for (int64_t i = 0; i < n_tab; ++i) ++start[max_cnt - cnt[i] + 1];
+            for (size_t c = 1; c < start.size(); ++c) start[c] += start[c - 1];
+            order.resize(static_cast<size_t>(n_tab));
+            for (int64_t i = 0; i < n_tab; ++i) order[start[max_cnt - cnt[i]]++] = static_cast<int32_t>(i);
+        }
+        if (hot_phases == 0) {
+            // Automatic.  The hash classes win while L2 can hold what matters of a class under plain LRU;
+            // when gathers are spread so evenly that the most gathered rows of one phase get less than
+            // half of them (measured: the 2.4 M-node R-MAT of the configs, 41 %, 4-8 % faster with
+            // phases; the others, 69-86 %, 5-10 % slower), explicit hot phases do better.
+            int64_t top = 0, all = static_cast<int64_t>(p->local_col.size()) + static_cast<int64_t>(p->remote_col.size());
+            for (int64_t r = 0; r < std::min<int64_t>(n_tab, per_phase); ++r) top += cnt[order[r]];
+            hot_phases = (all > 0 && 2 * top < all) ? kAutoHotPhases : -1;
+        }
+        p->class_mode = hot_phases < 0 ? 1 : 2;
+        if (hot_phases < 0) {
+            n_phase = 1;
+            for (int64_t i = 0; i < n_own; ++i) p->src_class[i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
+            for (int64_t i = 0; i < num_halo; ++i) p->src_class[n_own + i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
+        } else if (n_tab > 0) {
+            const int64_t limit = std::min<int64_t>(n_tab, per_phase * hot_phases);
+            int64_t r = 0;
+            for (; r < limit && cnt[order[r]] >= hot_min_count; ++r)
+                p->src_class[order[r]] = static_cast<uint8_t>((r / per_phase) * kXcd + r % kXcd);
+            n_phase = static_cast<int>(ceil_div(r, per_phase));
+        }
+    }
+    p->n_phases = n_phase;
+    const int n_hot = n_phase * kXcd;                        // hot classes; class index n_hot = cold
+
+    // ---- work decomposition ----------------------------------------------------------
+    // short rows: several per wavefront; whole rows: one item; long rows: cut at
+    // multiples of dist neighbour partitions, item k pairing local run k with remote run k.
+    // Rows with at least xcd_min_deg neighbours are first regrouped by source class: each
+    // class with at least min_piece neighbours becomes a piece with its own items (the rest
+    // joins the row's cold piece), and the launch order below hands the items of class
+    // (phase, x) to XCD x, phase by phase.
+    const int64_t run = static_cast<int64_t>(ps) * dist;   // neighbours per run
+    if (use_classes) { p->sched_local_col = p->local_col; p->sched_remote_col = p->remote_col; }
+    std::vector<std::vector<WorkItem>> bucket(static_cast<size_t>(std::max(n_hot, 1)));   // hot items by class
+    std::vector<WorkItem> cold;                              // cold pieces and whole rows
+    std::vector<std::vector<int32_t>> by_len(short_max >= 0 ? short_max + 1 : 0);
+    auto item_work = [](const WorkItem &it) { return static_cast<int64_t>(it.lend - it.lbeg) + (it.rend - it.rbeg) + 8; };
+    std::vector<int32_t> n_in(static_cast<size_t>(n_hot) + 1), lcut(static_cast<size_t>(n_hot) + 2), rcut(static_cast<size_t>(n_hot) + 2), pos(static_cast<size_t>(n_hot) + 1), tmp;
+    std::vector<uint8_t> final_class(static_cast<size_t>(n_hot) + 1);
+    // stable counting sort of col[b, e) by final class of the table row `base + col`; cut[c] = start of class c
+    auto regroup = [&](std::vector<int32_t> &col, int32_t b, int32_t e, int64_t base, std::vector<int32_t> &cut) {
+        std::fill(pos.begin(), pos.end(), 0);
+        for (int32_t i = b; i < e; ++i) ++pos[final_class[std::min<int>(p->src_class[base + col[i]], n_hot)]];
+        cut[0] = b;
+        for (int c = 0; c <= n_hot; ++c) cut[c + 1] = cut[c] + pos[c];
+        tmp.assign(col.begin() + b, col.begin() + e);
+        for (int c = 0; c <= n_hot; ++c) pos[c] = cut[c];
+        for (int32_t u : tmp) col[pos[final_class[std::min<int>(p->src_class[base + u], n_hot)]]++] = u;
+    };
+    std::vector<std::pair<WorkItem, int>> row_items;         // item, class (n_hot = cold)
+    for (int64_t v = 0; v < n_own; ++v) {
+        const int32_t l0 = p->local_row_ptr[v], l1 = p->local_row_ptr[v + 1];
+        const int32_t r0 = p->remote_row_ptr[v], r1 = p->remote_row_ptr[v + 1];
+        const int64_t dl = l1 - l0, dr = r1 - r0;
+        p->n_groups_local += ceil_div(dl, ps);
+        p->n_groups_remote += ceil_div(dr, ps);
+        if (short_max >= 0 && dl + dr <= short_max) { by_len[dl + dr].push_back(static_cast<int32_t>(v)); continue; }
+        // the pieces of this row: one per surviving class if it is regrouped, otherwise the whole row
+        int first_piece = n_hot, n_piece_end = n_hot + 1;     // default: only the cold piece = the whole row
+        if (use_classes && n_hot > 0 && dl + dr >= xcd_min_deg) {
+            std::fill(n_in.begin(), n_in.end(), 0);
+            for (int32_t i = l0; i < l1; ++i) ++n_in[std::min<int>(p->src_class[p->local_col[i]], n_hot)];
+            for (int32_t i = r0; i < r1; ++i) ++n_in[std::min<int>(p->src_class[n_own + p->remote_col[i]], n_hot)];
+            for (int c = 0; c < n_hot; ++c) final_class[c] = static_cast<uint8_t>(n_in[c] >= min_piece ? c : n_hot);
+            final_class[n_hot] = static_cast<uint8_t>(n_hot);
+            regroup(p->sched_local_col, l0, l1, 0, lcut);
+            regroup(p->sched_remote_col, r0, r1, n_own, rcut);
+            first_piece = 0;
+        } else {
+            lcut[n_hot] = l0; lcut[n_hot + 1] = l1; rcut[n_hot] = r0; rcut[n_hot + 1] = r1;
+        }
+        row_items.clear();
+        for (int c = first_piece; c < n_piece_end; ++c) {
+            const int64_t pl = lcut[c + 1] - lcut[c], pr = rcut[c + 1] - rcut[c];
+            if (pl + pr == 0 && !(c == n_hot && row_items.empty())) continue;   // an empty row still needs its one item
+            const int64_t n_it = std::max<int64_t>(1, std::max(ceil_div(pl, run), ceil_div(pr, run)));
+            for (int64_t k = 0; k < n_it; ++k) {
+                WorkItem it;
+                it.row = static_cast<int32_t>(v);
+                it.lbeg = static_cast<int32_t>(std::min<int64_t>(lcut[c] + k * run, lcut[c + 1]));
+                it.lend = static_cast<int32_t>(std::min<int64_t>(lcut[c] + (k + 1) * run, lcut[c + 1]));
+                it.rbeg = static_cast<int32_t>(std::min<int64_t>(rcut[c] + k * run, rcut[c + 1]));
+                it.rend = static_cast<int32_t>(std::min<int64_t>(rcut[c] + (k + 1) * run, rcut[c + 1]));
+                it.slot = -1;
+                it.pad0 = it.pad1 = 0;
+                row_items.emplace_back(it, c);
+            }
+        }
+        if (row_items.size() > 1) {                      // partial sums + fix-up
+            SplitRow sr{static_cast<int32_t>(v), static_cast<int32_t>(p->n_split_items), static_cast<int32_t>(row_items.size()), 0};
+            p->split_rows.push_back(sr);
+            for (auto &ri : row_items) ri.first.slot = static_cast<int32_t>(p->n_split_items++);
+        }
+        for (auto &ri : row_items) {
+            if (ri.second < n_hot) bucket[ri.second].push_back(ri.first);
+            else cold.push_back(ri.first);
+        }
+    }
+    // heavy items first, so that the tail of the launch is made of small ones
+    std::stable_sort(cold.begin(), cold.end(), [&](const WorkItem &a, const WorkItem &b) { return item_work(a) > item_work(b); });
+    if (!use_classes) {
+        p->items = std::move(cold);
+    } else {
+        // XCD x takes the hot items of classes (0, x), (1, x), ... in that order; cold items then
+        // go, largest first, to whichever XCD has the least work so far (a gather that hits in L2
+        // is taken as half the cost of one that does not)
+        std::vector<std::vector<WorkItem>> queue(kXcd);
+        std::vector<int64_t> queue_work(kXcd, 0);
+        for (int c = 0; c < n_hot; ++c) {
+            std::vector<WorkItem> &q = queue[c % kXcd];
+            for (const WorkItem &it : bucket[c]) queue_work[c % kXcd] += item_work(it);
+            q.insert(q.end(), bucket[c].begin(), bucket[c].end());
+        }
+        for (int c = 0; c < kXcd; ++c) queue_work[c] /= 2;
+        for (const WorkItem &it : cold) {
+            const int c = static_cast<int>(std::min_element(queue_work.begin(), queue_work.end()) - queue_work.begin());
+            queue[c].push_back(it);
+            queue_work[c] += item_work(it);
+        }
+        // launch order: workgroup b (wpb items) runs on XCD b mod kXcd; pad with empty items
+        size_t longest = 0;
+        for (auto &q : queue) longest = std::max(longest, q.size());
+        longest = (longest + wpb - 1) / wpb * wpb;
+        const WorkItem dummy{-1, 0, 0, 0, 0, -1, 0, 0};
+        for (auto &q : queue) q.resize(longest, dummy);
+        p->items.reserve(longest * kXcd);
+        for (size_t g = 0; g < longest; g += wpb)
+            for (int c = 0; c < kXcd; ++c)
+                p->items.insert(p->items.end(), queue[c].begin() + g, queue[c].begin() + g + wpb);
+    }
+    for (int32_t len = short_max; len >= 0; --len)         // longest first, isolated rows last
+        p->short_rows.insert(p->short_rows.end(), by_len[len].begin(), by_len[len].end());
+}
+
+}  // namespace mgg
+
+using namespace mgg;
+
+extern "C" {
+
+const char *mgg_last_error(void) { return mgg::last_error(); }
+const char *mgg_version(void) { return "mgg-mi355x 0.1 (gfx950)"; }
+
+mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, const int32_t *col_idx,
+                                 int32_t num_parts, int32_t part_id, const int64_t *bounds,
+                                 const mgg_build_opts_t *opts, mgg_partition_t **out)
+{
+    if (!out) return fail(MGG_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (num_nodes < 0 || !row_ptr) return fail(MGG_ERR_INVALID_ARG, "num_nodes < 0 or row_ptr is NULL");
+    if (num_nodes > INT32_MAX - 1) return fail(MGG_ERR_UNSUPPORTED, "more than 2^31-2 nodes");
+    if (num_parts < 1 || part_id < 0 || part_id >= num_parts)
+        return fail(MGG_ERR_INVALID_ARG, "part_id %d outside [0, %d)", part_id, num_parts);
+    Knobs knobs;
+    {
+        mgg_status_t st = parse_opts(opts, &knobs);
+        if (st != MGG_OK) return st;
+    }
+    const int32_t host_only = knobs.host_only;
 
     // ---- validate the graph ------------------------------------------------------------
     if (row_ptr[0] != 0) return fail(MGG_ERR_BAD_GRAPH, "row_ptr[0] != 0");
@@ -186,8 +377,6 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
     try {
         p->num_nodes = num_nodes; p->lb = lb; p->ub = ub; p->n_own = n_own;
         p->num_parts = num_parts; p->part_id = part_id;
-        p->ps = ps; p->dist = dist; p->short_max = short_max; p->xcd_min_deg = xcd_min_deg; p->wpb = wpb;
-        p->hot_rows = hot_rows; p->hot_phases = hot_phases; p->min_piece = min_piece; p->hot_min_count = hot_min_count;
 
         // ---- pass 1: count local / remote per owned row, mark halo nodes -----------------
         std::vector<uint8_t> is_halo(static_cast<size_t>(num_nodes), 0);
@@ -248,167 +437,7 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
             p->dinv_halo[h] = static_cast<float>(1.0 / std::sqrt(static_cast<double>(p->deg_halo[h]) + 1.0));
         }
 
-        // ---- source classes -------------------------------------------------------------
-        // Every row of the two embedding tables gets a class.  hot_phases < 0: a hash of its index, 8
-        // classes, one per XCD, no cold class.  With hot_phases >= 1 (0 chooses between the two) the class is
-        // either (phase, XCD) -- "hot" -- or cold, and hot classes are filled in order of popularity (how many owned rows gather the
-        // table row): the 8*hot_rows most gathered rows form phase 0, dealt round-robin to the
-        // 8 XCDs, the next 8*hot_rows phase 1, and so on.  An XCD works through its phases in
-        // order, so at any time its L2 only has to hold hot_rows table rows, all of which are
-        // gathered many times.
-        const bool use_classes = xcd_min_deg > 0;
-        const int64_t n_tab = n_own + num_halo;                  // local rows first, then halo slots
-        int n_phase = 0;
-        if (use_classes) {
-            p->src_class.assign(static_cast<size_t>(n_tab), kColdClass);
-            std::vector<int32_t> order;                          // table rows, most gathered first
-            std::vector<int32_t> cnt;
-            const int64_t per_phase = static_cast<int64_t>(kXcd) * hot_rows;
-            if (hot_phases >= 0 && n_tab > 0) {
-                cnt.assign(static_cast<size_t>(n_tab), 0);
-                for (int32_t u : p->local_col) ++cnt[u];
-                for (int32_t u : p->remote_col) ++cnt[n_own + u];
-                // counting sort by gather count (ties: lower index first)
-                const int32_t max_cnt = *std::max_element(cnt.begin(), cnt.end());
-                std::vector<int64_t> start(static_cast<size_t>(max_cnt) + 2, 0);
-                for (int64_t i = 0; i < n_tab; ++i) ++start[max_cnt - cnt[i] + 1];
-                for (size_t c = 1; c < start.size(); ++c) start[c] += start[c - 1];
-                order.resize(static_cast<size_t>(n_tab));
-                for (int64_t i = 0; i < n_tab; ++i) order[start[max_cnt - cnt[i]]++] = static_cast<int32_t>(i);
-            }
-            if (hot_phases == 0) {
-                // Automatic.  The hash classes win while L2 can hold what matters of a class under plain LRU;
-                // when gathers are spread so evenly that the most gathered rows of one phase get less than
-                // half of them (measured: the 2.4 M-node R-MAT of the configs, 41 %, 4-8 % faster with
-                // phases; the others, 69-86 %, 5-10 % slower), explicit hot phases do better.
-                int64_t top = 0, all = static_cast<int64_t>(p->local_col.size()) + static_cast<int64_t>(p->remote_col.size());
-                for (int64_t r = 0; r < std::min<int64_t>(n_tab, per_phase); ++r) top += cnt[order[r]];
-                hot_phases = (all > 0 && 2 * top < all) ? kAutoHotPhases : -1;
-            }
-            p->class_mode = hot_phases < 0 ? 1 : 2;
-            if (hot_phases < 0) {
-                n_phase = 1;
-                for (int64_t i = 0; i < n_own; ++i) p->src_class[i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
-                for (int64_t i = 0; i < num_halo; ++i) p->src_class[n_own + i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
-            } else if (n_tab > 0) {
-                const int64_t limit = std::min<int64_t>(n_tab, per_phase * hot_phases);
-                int64_t r = 0;
-                for (; r < limit && cnt[order[r]] >= hot_min_count; ++r)
-                    p->src_class[order[r]] = static_cast<uint8_t>((r / per_phase) * kXcd + r % kXcd);
-                n_phase = static_cast<int>(ceil_div(r, per_phase));
-            }
-        }
-        p->n_phases = n_phase;
-        const int n_hot = n_phase * kXcd;                        // hot classes; class index n_hot = cold
-
-        // ---- work decomposition ----------------------------------------------------------
-        // short rows: several per wavefront; whole rows: one item; long rows: cut at
-        // multiples of dist neighbour partitions, item k pairing local run k with remote run k.
-        // Rows with at least xcd_min_deg neighbours are first regrouped by source class: each
-        // class with at least min_piece neighbours becomes a piece with its own items (the rest
-        // joins the row's cold piece), and the launch order below hands the items of class
-        // (phase, x) to XCD x, phase by phase.
-        const int64_t run = static_cast<int64_t>(ps) * dist;   // neighbours per run
-        if (use_classes) { p->sched_local_col = p->local_col; p->sched_remote_col = p->remote_col; }
-        std::vector<std::vector<WorkItem>> bucket(static_cast<size_t>(std::max(n_hot, 1)));   // hot items by class
-        std::vector<WorkItem> cold;                              // cold pieces and whole rows
-        std::vector<std::vector<int32_t>> by_len(short_max >= 0 ? short_max + 1 : 0);
-        auto item_work = [](const WorkItem &it) { return static_cast<int64_t>(it.lend - it.lbeg) + (it.rend - it.rbeg) + 8; };
-        std::vector<int32_t> n_in(static_cast<size_t>(n_hot) + 1), lcut(static_cast<size_t>(n_hot) + 2), rcut(static_cast<size_t>(n_hot) + 2), pos(static_cast<size_t>(n_hot) + 1), tmp;
-        std::vector<uint8_t> final_class(static_cast<size_t>(n_hot) + 1);
-        // stable counting sort of col[b, e) by final class of the table row `base + col`; cut[c] = start of class c
-        auto regroup = [&](std::vector<int32_t> &col, int32_t b, int32_t e, int64_t base, std::vector<int32_t> &cut) {
-            std::fill(pos.begin(), pos.end(), 0);
-            for (int32_t i = b; i < e; ++i) ++pos[final_class[std::min<int>(p->src_class[base + col[i]], n_hot)]];
-            cut[0] = b;
-            for (int c = 0; c <= n_hot; ++c) cut[c + 1] = cut[c] + pos[c];
-            tmp.assign(col.begin() + b, col.begin() + e);
-            for (int c = 0; c <= n_hot; ++c) pos[c] = cut[c];
-            for (int32_t u : tmp) col[pos[final_class[std::min<int>(p->src_class[base + u], n_hot)]]++] = u;
-        };
-        std::vector<std::pair<WorkItem, int>> row_items;         // item, class (n_hot = cold)
-        for (int64_t v = 0; v < n_own; ++v) {
-            const int32_t l0 = p->local_row_ptr[v], l1 = p->local_row_ptr[v + 1];
-            const int32_t r0 = p->remote_row_ptr[v], r1 = p->remote_row_ptr[v + 1];
-            const int64_t dl = l1 - l0, dr = r1 - r0;
-            p->n_groups_local += ceil_div(dl, ps);
-            p->n_groups_remote += ceil_div(dr, ps);
-            if (short_max >= 0 && dl + dr <= short_max) { by_len[dl + dr].push_back(static_cast<int32_t>(v)); continue; }
-            // the pieces of this row: one per surviving class if it is regrouped, otherwise the whole row
-            int first_piece = n_hot, n_piece_end = n_hot + 1;     // default: only the cold piece = the whole row
-            if (use_classes && n_hot > 0 && dl + dr >= xcd_min_deg) {
-                std::fill(n_in.begin(), n_in.end(), 0);
-                for (int32_t i = l0; i < l1; ++i) ++n_in[std::min<int>(p->src_class[p->local_col[i]], n_hot)];
-                for (int32_t i = r0; i < r1; ++i) ++n_in[std::min<int>(p->src_class[n_own + p->remote_col[i]], n_hot)];
-                for (int c = 0; c < n_hot; ++c) final_class[c] = static_cast<uint8_t>(n_in[c] >= min_piece ? c : n_hot);
-                final_class[n_hot] = static_cast<uint8_t>(n_hot);
-                regroup(p->sched_local_col, l0, l1, 0, lcut);
-                regroup(p->sched_remote_col, r0, r1, n_own, rcut);
-                first_piece = 0;
-            } else {
-                lcut[n_hot] = l0; lcut[n_hot + 1] = l1; rcut[n_hot] = r0; rcut[n_hot + 1] = r1;
-            }
-            row_items.clear();
-            for (int c = first_piece; c < n_piece_end; ++c) {
-                const int64_t pl = lcut[c + 1] - lcut[c], pr = rcut[c + 1] - rcut[c];
-                if (pl + pr == 0 && !(c == n_hot && row_items.empty())) continue;   // an empty row still needs its one item
-                const int64_t n_it = std::max<int64_t>(1, std::max(ceil_div(pl, run), ceil_div(pr, run)));
-                for (int64_t k = 0; k < n_it; ++k) {
-                    WorkItem it;
-                    it.row = static_cast<int32_t>(v);
-                    it.lbeg = static_cast<int32_t>(std::min<int64_t>(lcut[c] + k * run, lcut[c + 1]));
-                    it.lend = static_cast<int32_t>(std::min<int64_t>(lcut[c] + (k + 1) * run, lcut[c + 1]));
-                    it.rbeg = static_cast<int32_t>(std::min<int64_t>(rcut[c] + k * run, rcut[c + 1]));
-                    it.rend = static_cast<int32_t>(std::min<int64_t>(rcut[c] + (k + 1) * run, rcut[c + 1]));
-                    it.slot = -1;
-                    it.pad0 = it.pad1 = 0;
-                    row_items.emplace_back(it, c);
-                }
-            }
-            if (row_items.size() > 1) {                      // partial sums + fix-up
-                SplitRow sr{static_cast<int32_t>(v), static_cast<int32_t>(p->n_split_items), static_cast<int32_t>(row_items.size()), 0};
-                p->split_rows.push_back(sr);
-                for (auto &ri : row_items) ri.first.slot = static_cast<int32_t>(p->n_split_items++);
-            }
-            for (auto &ri : row_items) {
-                if (ri.second < n_hot) bucket[ri.second].push_back(ri.first);
-                else cold.push_back(ri.first);
-            }
-        }
-        // heavy items first, so that the tail of the launch is made of small ones
-        std::stable_sort(cold.begin(), cold.end(), [&](const WorkItem &a, const WorkItem &b) { return item_work(a) > item_work(b); });
-        if (!use_classes) {
-            p->items = std::move(cold);
-        } else {
-            // XCD x takes the hot items of classes (0, x), (1, x), ... in that order; cold items then
-            // go, largest first, to whichever XCD has the least work so far (a gather that hits in L2
-            // is taken as half the cost of one that does not)
-            std::vector<std::vector<WorkItem>> queue(kXcd);
-            std::vector<int64_t> queue_work(kXcd, 0);
-            for (int c = 0; c < n_hot; ++c) {
-                std::vector<WorkItem> &q = queue[c % kXcd];
-                for (const WorkItem &it : bucket[c]) queue_work[c % kXcd] += item_work(it);
-                q.insert(q.end(), bucket[c].begin(), bucket[c].end());
-            }
-            for (int c = 0; c < kXcd; ++c) queue_work[c] /= 2;
-            for (const WorkItem &it : cold) {
-                const int c = static_cast<int>(std::min_element(queue_work.begin(), queue_work.end()) - queue_work.begin());
-                queue[c].push_back(it);
-                queue_work[c] += item_work(it);
-            }
-            // launch order: workgroup b (wpb items) runs on XCD b mod kXcd; pad with empty items
-            size_t longest = 0;
-            for (auto &q : queue) longest = std::max(longest, q.size());
-            longest = (longest + wpb - 1) / wpb * wpb;
-            const WorkItem dummy{-1, 0, 0, 0, 0, -1, 0, 0};
-            for (auto &q : queue) q.resize(longest, dummy);
-            p->items.reserve(longest * kXcd);
-            for (size_t g = 0; g < longest; g += wpb)
-                for (int c = 0; c < kXcd; ++c)
-                    p->items.insert(p->items.end(), queue[c].begin() + g, queue[c].begin() + g + wpb);
-        }
-        for (int32_t len = short_max; len >= 0; --len)         // longest first, isolated rows last
-            p->short_rows.insert(p->short_rows.end(), by_len[len].begin(), by_len[len].end());
+        build_schedule(p, knobs);
     } catch (const std::bad_alloc &) {
         delete p;
         return fail(MGG_ERR_ALLOC, "out of host memory while building the partition");
