@@ -367,6 +367,72 @@ def run_update_shapes(iters: int = 20, vendor: bool = True):
     return rows
 
 
+def run_embedding_bags(iters: int = 20, cpu_budget_s: float = 10.0):
+    """Embedding lookup + element-wise addition of a recommendation model (section 8.3) through the
+    aggregation path.  Synthetic stand-in for a click-log batch (the paper uses Criteo Kaggle, which is
+    not available here): 26 tables of 2^18 rows each, concatenated; a sample looks up one row in every
+    table, rows drawn from a Zipf-like law (exponent 1.05) per table; 2^20 samples; dim 64 fp32.  The
+    table is cut by rows over 4 GPUs, this GPU holds the first quarter and serves the rest from a halo
+    table of the distinct rows its samples need."""
+    import torch
+    import oracle
+    from paper_2209_06800_amd import binding
+    dev = "cuda:0"
+    n_tables, rows_per_table, n_bags, dim = 26, 1 << 18, 1 << 20, 64
+    table_rows = n_tables * rows_per_table
+    rng = np.random.default_rng(220906800 + 83)
+    # Zipf-like ranks by inverse transform on a truncated power law, then a fixed shuffle of ranks per table
+    u = rng.random((n_bags, n_tables))
+    a = 1.05
+    ranks = np.floor(((rows_per_table ** (1 - a) - 1) * u + 1) ** (1 / (1 - a))).astype(np.int64) - 1
+    ranks = np.clip(ranks, 0, rows_per_table - 1)
+    perm = np.stack([rng.permutation(rows_per_table) for _ in range(n_tables)])
+    idx = (perm[np.arange(n_tables)[None, :], ranks] + np.arange(n_tables)[None, :] * rows_per_table).astype(np.int32)
+    idx = np.sort(idx, axis=1).ravel()
+    ptr = np.arange(0, (n_bags + 1) * n_tables, n_tables, dtype=np.int64)
+    lo, hi = 0, table_rows // 4
+    t0 = time.time()
+    part = binding.mgg_build_bags(ptr, idx, table_rows, lo, hi)
+    info = part.info
+    hg = part.export()["halo_gid"]
+    log(f"[bags] {n_bags} bags x {n_tables} lookups over {table_rows} rows x {dim}: local lookups {info.nnz_local}, remote "
+        f"{info.nnz_remote}, distinct remote rows {info.num_halo}, built in {time.time() - t0:.1f}s")
+    table = rng.standard_normal((table_rows, dim), dtype=np.float32)
+    t_local, t_halo = to_dev(table[lo:hi], dev), to_dev(table[hg], dev)
+    out = torch.empty((n_bags, dim), dtype=torch.float32, device=dev)
+    for _ in range(3):
+        binding.mgg_bag_sum(part, t_local, t_halo, out=out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        binding.mgg_bag_sum(part, t_local, t_halo, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    lookups = int(info.nnz_local + info.nnz_remote)
+    model_bytes = lookups * (dim * 4 + 4) + n_bags * (dim * 4 + 8)
+    # check a sample of bags against the oracle and time the oracle on a bounded sample
+    sel = np.sort(rng.choice(n_bags, size=4096, replace=False))
+    sub_ptr = np.arange(0, (sel.size + 1) * n_tables, n_tables, dtype=np.int64)
+    sub_idx = idx.reshape(n_bags, n_tables)[sel].ravel()
+    ref = oracle.bag_sum(sub_ptr, sub_idx, table)
+    got = out[torch.from_numpy(sel).to(dev)].cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref).max()
+    n_cpu = min(n_bags, 1 << 18)
+    t0 = time.perf_counter()
+    oracle.bag_sum(ptr[:n_cpu + 1], idx[:n_cpu * n_tables], table)
+    cpu_s = time.perf_counter() - t0
+    res = {"workload": "embedding_bags_26x2^18_rows_dim64_2^20_samples", "lookups": lookups, "bags": n_bags,
+           "local_share": round(info.nnz_local / lookups, 3), "num_halo": int(info.num_halo), "ms": round(ms, 4),
+           "glookups_per_s": round(lookups / ms / 1e6, 2), "gather_model_gbs": round(model_bytes / ms / 1e6, 1),
+           "frac_of_hbm_peak": round(model_bytes / ms / 1e6 / HBM_PEAK_GBS, 3), "max_abs_err_vs_oracle_on_4096_bags": float(err),
+           "cpu_oracle_glookups_per_s": round(n_cpu * n_tables / cpu_s / 1e9, 4), "cpu_cores": oracle.num_threads()}
+    log(f"[bags] {ms:.4f} ms per batch, {res['glookups_per_s']} GLookups/s, gather-model {res['gather_model_gbs']} GB/s "
+        f"({res['frac_of_hbm_peak']} of 8 TB/s); max error on 4096 sampled bags {err:.2e}; oracle {res['cpu_oracle_glookups_per_s']} GLookups/s")
+    part.destroy()
+    return res
+
+
 def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 20.0, calibrate_copy: bool = False,
         cold_iters: int = 5, part_id=None, split: str = "nodes"):
     import torch
@@ -571,6 +637,8 @@ def main():
     ap.add_argument("--split", choices=["nodes", "edges"], default="nodes",
                     help="node ranges of the shares: equal node counts (default) or the edge-balanced split of Algorithm 1")
     ap.add_argument("--part-id", type=int, default=None, help="time another share of the graph than share 0")
+    ap.add_argument("--embedding-bags", action="store_true",
+                    help="time the embedding-bag sum of a synthetic recommendation-model batch (section 8.3) and exit")
     ap.add_argument("--update-shapes", action="store_true",
                     help="time mgg_update alone on the Update shapes of the five configs and exit")
     ap.add_argument("--no-vendor", action="store_true", help="with --update-shapes: skip the torch.matmul comparison")
@@ -586,6 +654,9 @@ def main():
         print("bench.py measures one GPU's share on one MI355X; multi-GPU runs are not part of this build "
               "(no collectives, no second GPU). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    if args.embedding_bags:
+        print(json.dumps(run_embedding_bags()), flush=True)
+        return
     if args.update_shapes:
         print(json.dumps({"update_shapes": run_update_shapes(vendor=not args.no_vendor)}), flush=True)
         return

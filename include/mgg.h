@@ -100,6 +100,8 @@ typedef struct {
     int64_t n_short_rows;                     /* rows handled several per wavefront          */
     int64_t n_items;                          /* wavefront work items incl. padding items     */
     int64_t n_split_rows, n_split_items;      /* rows cut into > 1 item, and those items     */
+    int64_t n_local_rows;                     /* rows of the local table: n_own, or the local slice of a bag partition */
+    int32_t is_bags;                          /* built by mgg_build_bags                      */
 } mgg_partition_info_t;
 
 /* Caller-allocated HOST buffers for mgg_partition_export(); a NULL member is skipped.
@@ -179,6 +181,29 @@ mgg_status_t mgg_aggregate(const mgg_partition_t *p, mgg_agg_t mode, float eps, 
 mgg_status_t mgg_aggregate_to(const mgg_partition_t *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
                               const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x,
                               mgg_dtype_t out_dtype, void *out, int64_t ld_out, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * mgg_build_bags / mgg_bag_sum -- section 8.3 ("Generality to other applications"): the embedding
+ * lookup of a recommendation model, rows of a large table fetched and added element-wise, with
+ * the table cut by rows over the GPUs.  The same path as the aggregation: a bag is an owned row
+ * without an embedding of its own, its lookups into this GPU's slice [local_lo, local_hi) of the
+ * table are the local neighbours, the others the remote ones, served from a halo table of the
+ * distinct remote rows in ascending row order (what an exchange with the owners would fill).
+ *
+ * mgg_build_bags: host, synchronous.  bag_ptr[num_bags+1] (int64, bag_ptr[0]==0) and
+ * bag_idx[bag_ptr[num_bags]] (int32 rows of the whole table, duplicates kept) are HOST pointers,
+ * not retained.  The handle works with mgg_partition_info / export / destroy (n_own = num_bags,
+ * lb / ub = the local slice, halo_gid = the remote rows) and with mgg_bag_sum only.
+ *
+ * mgg_bag_sum: out[b] = sum over the lookups of bag b of the table row, fp32 accumulation; empty
+ * bags give zero rows.  table_local [(local_hi-local_lo) x dim] and table_halo [num_halo x dim]
+ * DEVICE, same dtype and ld_x (either may be NULL when no lookup goes there); out [num_bags x dim]
+ * DEVICE, F32 or BF16.  Asynchronous on `stream`.  Errors as mgg_aggregate.
+ * ------------------------------------------------------------------------------------- */
+mgg_status_t mgg_build_bags(int64_t num_bags, const int64_t *bag_ptr, const int32_t *bag_idx, int64_t table_rows,
+                            int64_t local_lo, int64_t local_hi, const mgg_build_opts_t *opts, mgg_partition_t **out);
+mgg_status_t mgg_bag_sum(const mgg_partition_t *p, mgg_dtype_t x_dtype, const void *table_local, const void *table_halo,
+                         int32_t dim, int64_t ld_x, mgg_dtype_t out_dtype, void *out, int64_t ld_out, void *stream);
 
 /* ---------------------------------------------------------------------------------------
  * mgg_update -- section 1 (Update = a fully-connected layer), section 7 (X W, ReLU, MLP):

@@ -163,6 +163,17 @@ def aggregate(row_ptr, col, mode: str, x_local: np.ndarray, *, lb: int = 0, ub: 
     return out
 
 
+def bag_sum(bag_ptr, bag_idx, table: np.ndarray) -> np.ndarray:
+    """Sum of the looked-up rows of every bag over the whole table -> float64 [num_bags x dim]."""
+    bag_ptr, bag_idx = _i64(bag_ptr), _i32(bag_idx)
+    tab, code, ld = _table(table)
+    nb = bag_ptr.size - 1
+    out = np.zeros((nb, ld), dtype=np.float64)
+    _check(lib().mgg_oracle_bag_sum(C.c_int64(nb), _p(bag_ptr), _p(bag_idx), C.c_int64(table.shape[0]), C.c_int32(code), _p(tab),
+                                    C.c_int64(ld), C.c_int32(ld), _p(out)), "bag_sum")
+    return out
+
+
 def to_f64(t: np.ndarray) -> np.ndarray:
     """Exact widening of f32 / bf16-bit / f64 arrays to float64."""
     t = np.asarray(t)

@@ -16,6 +16,7 @@
  *   - fixed-size neighbour partitions of ps neighbours  section 4.1, Step-3
  *   - node-range ownership and ids rebased to zero .... section 4.2, Fig. 4
  *   - edge-balanced contiguous split ................. section 4.1, Step-1 / Algorithm 1
+ *   - embedding-bag sum (lookup + element-wise addition) section 8.3, generality to DLRM
  *
  * Conventions: graph = CSR (row_ptr int64[N+1], col int32[nnz]); row v lists the
  * nodes whose embeddings are summed into v.  A neighbour equal to the row's own id
@@ -323,6 +324,34 @@ int mgg_oracle_update(int64_t n_rows, const double *a, int64_t ld_a, int32_t d_i
         }
     }
     return 0;
+}
+
+/* ------------------------------------------------------------------------- *
+ * Embedding-bag sum (section 8.3, "Generality to other applications": embedding
+ * lookup followed by element-wise addition):
+ *     out[b][k] = sum over e in [bag_ptr[b], bag_ptr[b+1]) of table[bag_idx[e]][k]
+ * over the WHOLE table (no local / remote split here: where a row is stored does
+ * not change the sum).  Duplicates count with multiplicity, an empty bag gives zeros.
+ * table is [table_rows x ld] of x_dtype, out is double [num_bags x dim].
+ * ------------------------------------------------------------------------- */
+int mgg_oracle_bag_sum(int64_t num_bags, const int64_t *bag_ptr, const int32_t *bag_idx, int64_t table_rows,
+                       int32_t x_dtype, const void *table, int64_t ld, int32_t dim, double *out)
+{
+    if (num_bags < 0 || !bag_ptr || dim < 1 || ld < dim || (num_bags > 0 && !out)) return -2;
+    if (bag_ptr[0] != 0) return -3;
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t b = 0; b < num_bags; ++b) {
+        double *o = out + b * dim;
+        for (int32_t k = 0; k < dim; ++k) o[k] = 0.0;
+        if (bag_ptr[b + 1] < bag_ptr[b]) { bad = 1; continue; }
+        for (int64_t e = bag_ptr[b]; e < bag_ptr[b + 1]; ++e) {
+            int64_t u = bag_idx[e];
+            if (u < 0 || u >= table_rows) { bad = 1; continue; }
+            for (int32_t k = 0; k < dim; ++k) o[k] += load_elem(table, x_dtype, u * ld + k);
+        }
+    }
+    return bad ? -4 : 0;
 }
 
 /* ------------------------------------------------------------------------- *

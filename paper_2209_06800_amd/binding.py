@@ -27,7 +27,7 @@ _STATUS_NAME = ["OK", "INVALID_ARG", "BAD_GRAPH", "UNSUPPORTED", "ALLOC", "HIP"]
 
 EXPORTED_SYMBOLS = [
     "mgg_build_partition", "mgg_partition_info", "mgg_partition_export", "mgg_partition_destroy",
-    "mgg_aggregate", "mgg_aggregate_to", "mgg_update", "mgg_update_mlp", "mgg_layer_workspace_bytes", "mgg_layer_forward",
+    "mgg_aggregate", "mgg_aggregate_to", "mgg_build_bags", "mgg_bag_sum", "mgg_update", "mgg_update_mlp", "mgg_layer_workspace_bytes", "mgg_layer_forward",
     "mgg_split_edge_balanced", "mgg_set_option", "mgg_get_option", "mgg_time_aggregate",
     "mgg_model_evaluate", "mgg_tuner_create", "mgg_tuner_next", "mgg_tuner_report", "mgg_tuner_result",
     "mgg_tuner_table", "mgg_tuner_destroy", "mgg_tune_aggregate",
@@ -57,7 +57,8 @@ class PartitionInfo(C.Structure):
                 ("hot_rows", C.c_int32), ("n_phases", C.c_int32), ("min_piece", C.c_int32), ("hot_min_count", C.c_int32),
                 ("n_groups_local", C.c_int64), ("n_groups_remote", C.c_int64),
                 ("n_short_rows", C.c_int64), ("n_items", C.c_int64),
-                ("n_split_rows", C.c_int64), ("n_split_items", C.c_int64)]
+                ("n_split_rows", C.c_int64), ("n_split_items", C.c_int64),
+                ("n_local_rows", C.c_int64), ("is_bags", C.c_int32)]
 
 
 _ARRAY_FIELDS = ["local_row_ptr", "local_col", "remote_row_ptr", "remote_col", "halo_gid", "halo_peer_ptr",
@@ -114,6 +115,10 @@ def lib():
                                     C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
         L.mgg_aggregate_to.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_int32,
                                        C.c_int64, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
+        L.mgg_build_bags.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p,
+                                     C.POINTER(C.c_void_p)]
+        L.mgg_bag_sum.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int, C.c_void_p,
+                                  C.c_int64, C.c_void_p]
         L.mgg_update.argtypes = [C.c_int64, C.c_int, C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p,
                                  C.c_void_p, C.c_int32, C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
         L.mgg_update_mlp.argtypes = [C.c_int64, C.c_int, C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_int, C.c_void_p,
@@ -229,7 +234,7 @@ class Partition:
             "sched_local_col": i.nnz_local, "sched_remote_col": i.nnz_remote,
             "item_row": i.n_items, "item_lbeg": i.n_items, "item_lend": i.n_items, "item_rbeg": i.n_items,
             "item_rend": i.n_items, "item_slot": i.n_items,
-            "src_class_local": i.n_own, "src_class_halo": i.num_halo,
+            "src_class_local": i.n_local_rows, "src_class_halo": i.num_halo,
         }
         out = {k: np.zeros(max(int(n), 0), dtype=np.int64 if k == "halo_peer_ptr" else np.int32)
                for k, n in sizes.items()}
@@ -255,6 +260,33 @@ def mgg_build_partition(row_ptr: np.ndarray, col_idx: np.ndarray, num_parts: int
     _check(lib().mgg_build_partition(n, _np_ptr(row_ptr), _np_ptr(col_idx) if col_idx.size else None,
                                      num_parts, part_id, _np_ptr(b), C.byref(opts), C.byref(h)))
     return Partition(h.value)
+
+
+def mgg_build_bags(bag_ptr: np.ndarray, bag_idx: np.ndarray, table_rows: int, local_lo: int, local_hi: int, *,
+                   host_only: bool = False, **knobs) -> Partition:
+    """Partition for an embedding-bag sum: bags as owned rows, lookups split by the local slice of the table."""
+    bag_ptr = np.ascontiguousarray(bag_ptr, dtype=np.int64)
+    bag_idx = np.ascontiguousarray(bag_idx, dtype=np.int32)
+    opts = BuildOpts()
+    opts.host_only = int(host_only)
+    for key, v in knobs.items():
+        setattr(opts, key, v)
+    h = C.c_void_p()
+    _check(lib().mgg_build_bags(bag_ptr.size - 1, _np_ptr(bag_ptr), _np_ptr(bag_idx) if bag_idx.size else None, table_rows,
+                                local_lo, local_hi, C.byref(opts), C.byref(h)))
+    return Partition(h.value)
+
+
+def mgg_bag_sum(part: Partition, table_local, table_halo=None, *, out=None, out_dtype=None, dim: Optional[int] = None, stream=None):
+    """out[num_bags x dim] = sum of the looked-up rows of every bag."""
+    import torch
+    ref = table_local if table_local is not None else table_halo
+    dim = int(ref.shape[1]) if dim is None else dim
+    if out is None:
+        out = torch.empty((int(part.info.n_own), dim), dtype=out_dtype or torch.float32, device=ref.device)
+    _check(lib().mgg_bag_sum(part.handle, _torch_dtype_code(ref), _dev_ptr(table_local), _dev_ptr(table_halo), dim, _ld(ref),
+                             _torch_dtype_code(out), _dev_ptr(out), _ld(out), _stream(stream)))
+    return out
 
 
 def mgg_split_edge_balanced(row_ptr: np.ndarray, num_parts: int) -> np.ndarray:

@@ -48,6 +48,7 @@ struct AggArgs {
     int32_t gcn;             // 1: symmetric normalisation, 0: plain sum
     float self_w;            // GIN: 1 + eps
     int32_t out_bf16;
+    int32_t no_self;         // bags: the owned row has no embedding of its own, x_local is only a table
     int32_t out_vec_ok;      // out rows allow VEC-wide stores
     int32_t out_dim;         // columns of `out` that exist (<= nvec * VEC; the rest of the last vector is padding of the tables)
     int32_t phase;           // 0: local and remote lists in one launch; 1: local lists (+ self term) only;
@@ -167,7 +168,12 @@ __device__ __forceinline__ void write_final(const AggArgs &a, const Acc<K> &acc,
         const int vi = c * K::LPR + lis;
         if (vi < vend) {
             float xv[K::VEC], r[K::VEC];
-            unpack<K::BF16, K::VEC>(*reinterpret_cast<const typename K::raw *>(xs + static_cast<int64_t>(vi) * K::VEC), xv);
+            if (a.no_self) {
+#pragma unroll
+                for (int e = 0; e < K::VEC; ++e) xv[e] = 0.f;
+            } else {
+                unpack<K::BF16, K::VEC>(*reinterpret_cast<const typename K::raw *>(xs + static_cast<int64_t>(vi) * K::VEC), xv);
+            }
             if (a.phase == 2) {                 // second of two launches: add to the first one's result
 #pragma unroll
                 for (int e = 0; e < K::VEC; ++e) r[e] = (vi * K::VEC + e < a.out_dim ? o[vi * K::VEC + e] : 0.f) + dv * acc.v[c][e];
@@ -449,7 +455,8 @@ template <bool BF16>
 __global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_rows, int32_t n_split, int32_t dim, const float *scratch,
                                                        int64_t scratch_ld, const void *x_local, int64_t ld_x,
                                                        const float *dinv_own, int32_t gcn, float self_w, void *out_v, int32_t out_bf16,
-                                                       int64_t ld_out, int32_t out_vec_ok, int32_t phase, const float *bias, int32_t relu)
+                                                       int64_t ld_out, int32_t out_vec_ok, int32_t phase, const float *bias, int32_t relu,
+                                                       int32_t no_self)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int r_id = static_cast<int>(blockIdx.x) * kWavesPerBlock + static_cast<int>(threadIdx.x / kWave);
@@ -482,8 +489,9 @@ __global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_row
         for (int e = 0; e < 4; ++e) {
             r[e] = 0.f;
             if (k + e < dim) {
-                float xv;
-                if constexpr (BF16)
+                float xv = 0.f;
+                if (no_self) {
+                } else if constexpr (BF16)
                     xv = __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k + e]) << 16);
                 else
                     xv = static_cast<const float *>(x_local)[static_cast<int64_t>(sr.row) * ld_x + k + e];
@@ -628,7 +636,8 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
     a.n_short = static_cast<int32_t>(p->short_rows.size());
     a.ps = p->ps;
     a.gcn = mode == MGG_AGG_GCN_SYM;
-    a.self_w = 1.f + eps;
+    a.self_w = p->bags ? 0.f : 1.f + eps;
+    a.no_self = p->bags ? 1 : 0;
     a.bias = bias;
     a.out_dim = out_dim;
     a.relu = act == MGG_ACT_RELU;
@@ -670,10 +679,10 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
             const int32_t fix_vec_ok = (ld_out % 4 == 0) && aligned(out, a.out_bf16 ? 8 : 16);
             if (bf16)
                 hipLaunchKernelGGL(fixup_kernel<true>, fgrid, dim3(kBlock), 0, stream, p->d.split_rows, n_split, out_dim, p->d.scratch,
-                                   p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, a.out_bf16, ld_out, fix_vec_ok, a.phase, bias, a.relu);
+                                   p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, a.out_bf16, ld_out, fix_vec_ok, a.phase, bias, a.relu, a.no_self);
             else
                 hipLaunchKernelGGL(fixup_kernel<false>, fgrid, dim3(kBlock), 0, stream, p->d.split_rows, n_split, out_dim, p->d.scratch,
-                                   p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, a.out_bf16, ld_out, fix_vec_ok, a.phase, bias, a.relu);
+                                   p->d.scratch_ld, x_local, ld_x, p->d.dinv_own, a.gcn, a.self_w, out, a.out_bf16, ld_out, fix_vec_ok, a.phase, bias, a.relu, a.no_self);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return hip_fail(e, "fix-up kernel launch");
         }

@@ -21,14 +21,16 @@ static inline bool dtype_ok(mgg_dtype_t t) { return t == MGG_F32 || t == MGG_BF1
 
 static mgg_status_t check_aggregate(const mgg_partition *p, mgg_agg_t mode, mgg_dtype_t x_dtype, const void *x_local,
                                     const void *x_halo, int32_t dim, int64_t ld_x, const void *out, int64_t ld_out,
-                                    mgg_dtype_t out_dtype = MGG_F32)
+                                    mgg_dtype_t out_dtype = MGG_F32, bool bags_call = false)
 {
     if (!p) return fail(MGG_ERR_INVALID_ARG, "partition is NULL");
     if (p->device < 0) return fail(MGG_ERR_INVALID_ARG, "partition was built host-only");
+    if (p->bags != bags_call) return fail(MGG_ERR_INVALID_ARG, p->bags ? "a bag partition takes mgg_bag_sum" : "mgg_bag_sum needs a partition built by mgg_build_bags");
     if (mode != MGG_AGG_GCN_SYM && mode != MGG_AGG_GIN_SUM) return fail(MGG_ERR_INVALID_ARG, "unknown aggregation mode");
     if (!dtype_ok(x_dtype)) return fail(MGG_ERR_INVALID_ARG, "unknown dtype");
     if (dim < 1 || ld_x < dim || ld_out < dim) return fail(MGG_ERR_INVALID_ARG, "dim %d, ld_x %lld, ld_out %lld", dim, (long long)ld_x, (long long)ld_out);
-    if (p->n_own > 0 && (!x_local || !out)) return fail(MGG_ERR_INVALID_ARG, "x_local or out is NULL");
+    if (p->n_own > 0 && !out) return fail(MGG_ERR_INVALID_ARG, "out is NULL");
+    if ((p->bags ? !p->local_col.empty() : p->n_own > 0) && !x_local) return fail(MGG_ERR_INVALID_ARG, "x_local is NULL");
     if (!p->halo_gid.empty() && !x_halo) return fail(MGG_ERR_INVALID_ARG, "x_halo is NULL but the partition has %zu halo rows", p->halo_gid.size());
     const size_t esz = x_dtype == MGG_BF16 ? 2 : 4;
     if (!dtype_ok(out_dtype)) return fail(MGG_ERR_INVALID_ARG, "unknown output dtype");
@@ -118,6 +120,18 @@ mgg_status_t mgg_aggregate_to(const mgg_partition_t *p, mgg_agg_t mode, float ep
     if (p->n_own == 0) return MGG_OK;
     return launch_aggregate(p, mode, eps, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out, static_cast<hipStream_t>(stream), nullptr,
                             MGG_ACT_NONE, 0, out_dtype);
+}
+
+mgg_status_t mgg_bag_sum(const mgg_partition_t *p, mgg_dtype_t x_dtype, const void *table_local, const void *table_halo, int32_t dim,
+                         int64_t ld_x, mgg_dtype_t out_dtype, void *out, int64_t ld_out, void *stream)
+{
+    mgg_status_t s = check_aggregate(p, MGG_AGG_GIN_SUM, x_dtype, table_local, table_halo, dim, ld_x, out, ld_out, out_dtype, true);
+    if (s != MGG_OK) return s;
+    if (p->n_own == 0) return MGG_OK;
+    // a kernel argument must not be NULL even when no bag looks into the local slice
+    const void *tl = table_local ? table_local : (table_halo ? table_halo : out);
+    return launch_aggregate(p, MGG_AGG_GIN_SUM, -1.f, x_dtype, tl, table_halo, dim, ld_x, out, ld_out, static_cast<hipStream_t>(stream),
+                            nullptr, MGG_ACT_NONE, 0, out_dtype);
 }
 
 mgg_status_t mgg_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in,

@@ -60,6 +60,8 @@ struct DeviceArrays {
 
 struct mgg_partition {
     int64_t num_nodes = 0, lb = 0, ub = 0, n_own = 0;
+    int64_t n_local_rows = 0;         // rows of the local table: n_own for a graph partition, the local slice for bags
+    bool bags = false;                // built by mgg_build_bags: owned rows are bags, no self term, plain sums
     int32_t num_parts = 1, part_id = 0;
     int32_t ps = 64, dist = 8, short_max = 16, xcd_min_deg = -1, wpb = 4;
     int32_t hot_rows = 0, hot_phases = 0, n_phases = 0, min_piece = 0, hot_min_count = 0;

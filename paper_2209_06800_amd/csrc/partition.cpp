@@ -68,11 +68,11 @@ static mgg_status_t upload_all(mgg_partition *p)
         // coalesced stream instead of a 4-byte gather per neighbour
         const std::vector<int32_t> &lc = p->sched_local_col.empty() ? p->local_col : p->sched_local_col;
         const std::vector<int32_t> &rc = p->sched_remote_col.empty() ? p->remote_col : p->sched_remote_col;
-        std::vector<float> w(lc.size());
-        for (size_t i = 0; i < lc.size(); ++i) w[i] = p->dinv_own[lc[i]];
+        std::vector<float> w(p->bags ? 0 : lc.size());      // a bag partition has no factors: plain sums only
+        for (size_t i = 0; i < w.size(); ++i) w[i] = p->dinv_own[lc[i]];
         if ((s = upload(w, &p->d.w_local)) != MGG_OK) return s;
-        w.resize(rc.size());
-        for (size_t i = 0; i < rc.size(); ++i) w[i] = p->dinv_halo[rc[i]];
+        w.resize(p->bags ? 0 : rc.size());
+        for (size_t i = 0; i < w.size(); ++i) w[i] = p->dinv_halo[rc[i]];
         if ((s = upload(w, &p->d.w_remote)) != MGG_OK) return s;
     }
     if ((s = upload(p->short_rows, &p->d.short_rows)) != MGG_OK) return s;
@@ -151,6 +151,7 @@ static mgg_status_t parse_opts(const mgg_build_opts_t *opts, Knobs *k)
 static void build_schedule(mgg_partition *p, const Knobs &k)
 {
     const int64_t n_own = p->n_own, num_halo = static_cast<int64_t>(p->halo_gid.size());
+    const int64_t n_loc = p->n_local_rows;                  // rows of the local table (= n_own for a graph partition)
     const int32_t ps = k.ps, dist = k.dist, short_max = k.short_max, xcd_min_deg = k.xcd_min_deg, wpb = k.wpb;
     const int32_t hot_rows = k.hot_rows, min_piece = k.min_piece, hot_min_count = k.hot_min_count;
     int32_t hot_phases = k.hot_phases;
@@ -166,7 +167,7 @@ static void build_schedule(mgg_partition *p, const Knobs &k)
     // order, so at any time its L2 only has to hold hot_rows table rows, all of which are
     // gathered many times.
     const bool use_classes = xcd_min_deg > 0;
-    const int64_t n_tab = n_own + num_halo;                  // local rows first, then halo slots
+    const int64_t n_tab = n_loc + num_halo;                  // local rows first, then halo slots
     int n_phase = 0;
     if (use_classes) {
         p->src_class.assign(static_cast<size_t>(n_tab), kColdClass);
@@ -176,7 +177,7 @@ static void build_schedule(mgg_partition *p, const Knobs &k)
         if (hot_phases >= 0 && n_tab > 0) {
             cnt.assign(static_cast<size_t>(n_tab), 0);
             for (int32_t u : p->local_col) ++cnt[u];
-            for (int32_t u : p->remote_col) ++cnt[n_own + u];
+            for (int32_t u : p->remote_col) ++cnt[n_loc + u];
             // counting sort by gather count (ties: lower index first)
             const int32_t max_cnt = *std::max_element(cnt.begin(), cnt.end());
             std::vector<int64_t> start(static_cast<size_t>(max_cnt) + 2, 0);
@@ -197,8 +198,8 @@ static void build_schedule(mgg_partition *p, const Knobs &k)
         p->class_mode = hot_phases < 0 ? 1 : 2;
         if (hot_phases < 0) {
             n_phase = 1;
-            for (int64_t i = 0; i < n_own; ++i) p->src_class[i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
-            for (int64_t i = 0; i < num_halo; ++i) p->src_class[n_own + i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
+            for (int64_t i = 0; i < n_loc; ++i) p->src_class[i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
+            for (int64_t i = 0; i < num_halo; ++i) p->src_class[n_loc + i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
         } else if (n_tab > 0) {
             const int64_t limit = std::min<int64_t>(n_tab, per_phase * hot_phases);
             int64_t r = 0;
@@ -248,11 +249,11 @@ static void build_schedule(mgg_partition *p, const Knobs &k)
         if (use_classes && n_hot > 0 && dl + dr >= xcd_min_deg) {
             std::fill(n_in.begin(), n_in.end(), 0);
             for (int32_t i = l0; i < l1; ++i) ++n_in[std::min<int>(p->src_class[p->local_col[i]], n_hot)];
-            for (int32_t i = r0; i < r1; ++i) ++n_in[std::min<int>(p->src_class[n_own + p->remote_col[i]], n_hot)];
+            for (int32_t i = r0; i < r1; ++i) ++n_in[std::min<int>(p->src_class[n_loc + p->remote_col[i]], n_hot)];
             for (int c = 0; c < n_hot; ++c) final_class[c] = static_cast<uint8_t>(n_in[c] >= min_piece ? c : n_hot);
             final_class[n_hot] = static_cast<uint8_t>(n_hot);
             regroup(p->sched_local_col, l0, l1, 0, lcut);
-            regroup(p->sched_remote_col, r0, r1, n_own, rcut);
+            regroup(p->sched_remote_col, r0, r1, n_loc, rcut);
             first_piece = 0;
         } else {
             lcut[n_hot] = l0; lcut[n_hot + 1] = l1; rcut[n_hot] = r0; rcut[n_hot + 1] = r1;
@@ -375,7 +376,7 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
     mgg_partition *p = new (std::nothrow) mgg_partition;
     if (!p) return fail(MGG_ERR_ALLOC, "out of host memory");
     try {
-        p->num_nodes = num_nodes; p->lb = lb; p->ub = ub; p->n_own = n_own;
+        p->num_nodes = num_nodes; p->lb = lb; p->ub = ub; p->n_own = n_own; p->n_local_rows = n_own;
         p->num_parts = num_parts; p->part_id = part_id;
 
         // ---- pass 1: count local / remote per owned row, mark halo nodes -----------------
@@ -451,11 +452,79 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
     return MGG_OK;
 }
 
+mgg_status_t mgg_build_bags(int64_t num_bags, const int64_t *bag_ptr, const int32_t *bag_idx, int64_t table_rows,
+                            int64_t local_lo, int64_t local_hi, const mgg_build_opts_t *opts, mgg_partition_t **out)
+{
+    if (!out) return fail(MGG_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (num_bags < 0 || !bag_ptr || table_rows < 0) return fail(MGG_ERR_INVALID_ARG, "num_bags < 0, table_rows < 0 or bag_ptr is NULL");
+    if (num_bags > INT32_MAX - 1 || table_rows > INT32_MAX - 1) return fail(MGG_ERR_UNSUPPORTED, "more than 2^31-2 bags or table rows");
+    if (local_lo < 0 || local_hi < local_lo || local_hi > table_rows)
+        return fail(MGG_ERR_INVALID_ARG, "local slice [%lld, %lld) outside the table", (long long)local_lo, (long long)local_hi);
+    Knobs knobs;
+    {
+        mgg_status_t st = parse_opts(opts, &knobs);
+        if (st != MGG_OK) return st;
+    }
+    if (bag_ptr[0] != 0) return fail(MGG_ERR_BAD_GRAPH, "bag_ptr[0] != 0");
+    for (int64_t b = 0; b < num_bags; ++b)
+        if (bag_ptr[b + 1] < bag_ptr[b]) return fail(MGG_ERR_BAD_GRAPH, "bag_ptr decreases at bag %lld", (long long)b);
+    const int64_t nnz = bag_ptr[num_bags];
+    if (nnz >= INT32_MAX) return fail(MGG_ERR_UNSUPPORTED, "2^31-1 or more lookups");
+    if (nnz > 0 && !bag_idx) return fail(MGG_ERR_INVALID_ARG, "bag_idx is NULL");
+    for (int64_t e = 0; e < nnz; ++e)
+        if (bag_idx[e] < 0 || bag_idx[e] >= table_rows)
+            return fail(MGG_ERR_BAD_GRAPH, "table row %d at position %lld outside [0, %lld)", bag_idx[e], (long long)e, (long long)table_rows);
+
+    mgg_partition *p = new (std::nothrow) mgg_partition;
+    if (!p) return fail(MGG_ERR_ALLOC, "out of host memory");
+    try {
+        p->bags = true;
+        p->num_nodes = table_rows; p->lb = local_lo; p->ub = local_hi; p->n_own = num_bags; p->n_local_rows = local_hi - local_lo;
+        p->num_parts = 1; p->part_id = 0;
+        // rows of the table outside the local slice that are looked up, in ascending order, and their slots
+        std::vector<uint8_t> used(static_cast<size_t>(table_rows), 0);
+        for (int64_t e = 0; e < nnz; ++e)
+            if (bag_idx[e] < local_lo || bag_idx[e] >= local_hi) used[bag_idx[e]] = 1;
+        std::vector<int32_t> slot_of(static_cast<size_t>(table_rows), -1);
+        for (int64_t u = 0; u < table_rows; ++u)
+            if (used[u]) { slot_of[u] = static_cast<int32_t>(p->halo_gid.size()); p->halo_gid.push_back(static_cast<int32_t>(u)); }
+        p->halo_peer_ptr = {0, static_cast<int64_t>(p->halo_gid.size())};
+        p->local_row_ptr.assign(num_bags + 1, 0);
+        p->remote_row_ptr.assign(num_bags + 1, 0);
+        for (int64_t b = 0; b < num_bags; ++b) {
+            for (int64_t e = bag_ptr[b]; e < bag_ptr[b + 1]; ++e) {
+                const int32_t u = bag_idx[e];
+                if (u >= local_lo && u < local_hi) p->local_col.push_back(static_cast<int32_t>(u - local_lo));
+                else p->remote_col.push_back(slot_of[u]);
+            }
+            p->local_row_ptr[b + 1] = static_cast<int32_t>(p->local_col.size());
+            p->remote_row_ptr[b + 1] = static_cast<int32_t>(p->remote_col.size());
+        }
+        p->deg_own.resize(num_bags);
+        for (int64_t b = 0; b < num_bags; ++b) p->deg_own[b] = static_cast<int32_t>(bag_ptr[b + 1] - bag_ptr[b]);
+        p->deg_halo.assign(p->halo_gid.size(), 0);
+        p->dinv_own.assign(num_bags, 1.f);
+        p->dinv_halo.assign(p->halo_gid.size(), 1.f);
+        build_schedule(p, knobs);
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return fail(MGG_ERR_ALLOC, "out of host memory while building the bag partition");
+    }
+    if (!knobs.host_only) {
+        mgg_status_t s = upload_all(p);
+        if (s != MGG_OK) { free_device(p); delete p; return s; }
+    }
+    *out = p;
+    return MGG_OK;
+}
+
 mgg_status_t mgg_partition_info(const mgg_partition_t *p, mgg_partition_info_t *o)
 {
     if (!p || !o) return fail(MGG_ERR_INVALID_ARG, "NULL argument");
     std::memset(o, 0, sizeof *o);
     o->num_nodes = p->num_nodes; o->lb = p->lb; o->ub = p->ub; o->n_own = p->n_own;
+    o->n_local_rows = p->n_local_rows; o->is_bags = p->bags ? 1 : 0;
     o->nnz_local = static_cast<int64_t>(p->local_col.size());
     o->nnz_remote = static_cast<int64_t>(p->remote_col.size());
     o->num_halo = static_cast<int64_t>(p->halo_gid.size());
@@ -492,11 +561,11 @@ mgg_status_t mgg_partition_export(const mgg_partition_t *p, mgg_partition_arrays
     copy_out(p->sched_remote_col.empty() ? p->remote_col : p->sched_remote_col, a->sched_remote_col);
     if (a->src_class_local || a->src_class_halo) {
         // -1: cold (or no classes at all); otherwise phase * 8 + XCD
-        for (int64_t i = 0; i < p->n_own && a->src_class_local; ++i)
+        const int64_t nl = p->n_local_rows, nh = static_cast<int64_t>(p->halo_gid.size());
+        for (int64_t i = 0; i < nl && a->src_class_local; ++i)
             a->src_class_local[i] = p->src_class.empty() || p->src_class[i] == kColdClass ? -1 : p->src_class[i];
-        const int64_t nh = static_cast<int64_t>(p->halo_gid.size());
         for (int64_t i = 0; i < nh && a->src_class_halo; ++i)
-            a->src_class_halo[i] = p->src_class.empty() || p->src_class[p->n_own + i] == kColdClass ? -1 : p->src_class[p->n_own + i];
+            a->src_class_halo[i] = p->src_class.empty() || p->src_class[nl + i] == kColdClass ? -1 : p->src_class[nl + i];
     }
     for (size_t i = 0; i < p->items.size(); ++i) {
         const WorkItem &it = p->items[i];

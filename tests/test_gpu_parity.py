@@ -715,3 +715,38 @@ def test_layer_forward_in_a_hip_graph():
         torch.cuda.synchronize()
         assert torch.equal(out, want), f"replay {rep} differs from the eager result"
     part.destroy()
+
+
+# ----------------------------------------------------------------------------- embedding bags
+@pytest.mark.parametrize("dim,bf16,lo_hi,knobs", [(64, False, (0, 5000), {}), (16, False, (2000, 2600), dict(ps=8, dist=2)),
+                                                   (128, True, (0, 20000), {}), (47, False, (0, 0), dict(xcd_min_deg=16)),
+                                                   (100, True, (19000, 20000), dict(hot_phases=2, hot_rows=64)), (256, False, (3, 9), dict(short_max=-1))])
+def test_bag_sum(dim, bf16, lo_hi, knobs):
+    """Embedding-bag sum through the aggregation path (section 8.3): Zipf-distributed lookups, empty
+    and very large bags, the table cut into a local slice and a halo table of the distinct other rows."""
+    rng = np.random.default_rng(dim)
+    table_rows, n_bags = 20000, 3000
+    sizes = rng.integers(0, 60, size=n_bags)
+    sizes[:4] = [0, 1, 3000, 17]
+    ptr = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    idx = ((rng.zipf(1.1, size=ptr[-1]) - 1) % table_rows).astype(np.int32)
+    table = rng.standard_normal((table_rows, dim)).astype(np.float32)
+    if bf16:
+        table = inputs.to_bf16_bits(table)
+    lo, hi = lo_hi
+    part = binding.mgg_build_bags(ptr, idx, table_rows, lo, hi, **knobs)
+    hg = part.export()["halo_gid"]
+    t_local = to_dev(table[lo:hi]) if hi > lo else None
+    t_halo = to_dev(table[hg]) if hg.size else None
+    buf = torch.full((n_bags, dim + 3), float("nan"), dtype=torch.float32, device=DEV)
+    out = binding.mgg_bag_sum(part, t_local, t_halo, out=buf[:, :dim], dim=dim)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:, dim:]).all()
+    ref = oracle.bag_sum(ptr, idx, table)
+    scale = oracle.bag_sum(ptr, idx, np.abs(inputs.bf16_bits_to_f32(table)) if bf16 else np.abs(table))
+    got = to_host64(out)
+    assert np.all(np.abs(got - ref) <= 1e-6 * np.maximum(1.0, scale) + 1e-4 * np.abs(ref)), np.abs(got - ref).max()
+    assert np.all(got[0] == 0.0)                                    # the empty bag
+    with pytest.raises(binding.MggError):
+        binding.mgg_aggregate(part, "gin", t_local if t_local is not None else t_halo, t_halo)
+    part.destroy()

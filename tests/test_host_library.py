@@ -357,3 +357,33 @@ def test_partition_fuzz_against_oracle():
             _compare_with_oracle(row_ptr, col, parts, p, bounds, **opts)
 
     run()
+
+
+def test_bag_partition_structures():
+    """mgg_build_bags: lookups inside the local slice become local columns rebased to the slice, the
+    others halo slots over the distinct remote rows in ascending order -- rebuilt here with numpy."""
+    rng = np.random.default_rng(2)
+    table_rows, lo, hi = 3000, 700, 1900
+    sizes = rng.integers(0, 40, size=500)
+    sizes[:3] = [0, 1, 400]
+    ptr = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    idx = (rng.zipf(1.2, size=ptr[-1]) % table_rows).astype(np.int32)
+    for knobs in (dict(), dict(ps=4, dist=2, xcd_min_deg=8, short_max=2), dict(hot_phases=3, hot_rows=16, xcd_min_deg=4, min_piece=2)):
+        part = binding.mgg_build_bags(ptr, idx, table_rows, lo, hi, host_only=True, **knobs)
+        info, got = part.info, part.export()
+        assert (info.n_own, info.lb, info.ub, info.n_local_rows, info.is_bags) == (500, lo, hi, hi - lo, 1)
+        is_local = (idx >= lo) & (idx < hi)
+        halo = np.unique(idx[~is_local])
+        assert np.array_equal(got["halo_gid"], halo)
+        bag_of = np.repeat(np.arange(500), sizes)
+        assert np.array_equal(got["local_row_ptr"], np.concatenate([[0], np.cumsum(np.bincount(bag_of[is_local], minlength=500))]))
+        assert np.array_equal(got["remote_row_ptr"], np.concatenate([[0], np.cumsum(np.bincount(bag_of[~is_local], minlength=500))]))
+        assert np.array_equal(got["local_col"], idx[is_local] - lo)
+        assert np.array_equal(got["remote_col"], np.searchsorted(halo, idx[~is_local]))
+        assert np.array_equal(got["deg_own"], sizes)
+        _check_schedule(got, info, hot_by_popularity=info.class_mode == 2)
+        part.destroy()
+    # errors
+    assert _status(binding.mgg_build_bags, ptr, idx, table_rows, 10, 5, host_only=True) == binding.ERR_INVALID_ARG
+    assert _status(binding.mgg_build_bags, ptr, idx, 100, 0, 50, host_only=True) == binding.ERR_BAD_GRAPH
+    assert _status(binding.mgg_build_bags, np.array([0, 3, 2]), idx[:3], table_rows, 0, 5, host_only=True) == binding.ERR_BAD_GRAPH

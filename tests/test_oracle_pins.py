@@ -422,3 +422,31 @@ def test_update_softmax_pins():
     # hand value: softmax([0, ln 2, ln 5]) = [1, 2, 5] / 8
     np.testing.assert_allclose(oracle.update(np.array([[1.0]]), np.array([[0.0, np.log(2.0), np.log(5.0)]]), None, "softmax"),
                                [[0.125, 0.25, 0.625]], rtol=1e-15)
+
+
+def test_bag_sum_pins():
+    """Embedding-bag sum (section 8.3: embedding lookup followed by element-wise addition): the hand
+    value, numpy's segmented reduction, the equivalence with a GIN aggregation without the self term,
+    and the cases a wrong offset or a dropped duplicate would break."""
+    table = np.arange(12, dtype=np.float32).reshape(4, 3)
+    got = oracle.bag_sum([0, 2, 2, 5], [0, 3, 1, 1, 2], table)
+    assert got.tolist() == [[9.0, 11.0, 13.0], [0.0, 0.0, 0.0], [12.0, 15.0, 18.0]]      # rows 0+3; empty; rows 1+1+2
+    rng = np.random.default_rng(13)
+    t = rng.standard_normal((500, 7))
+    sizes = rng.integers(0, 9, size=200)
+    ptr = np.concatenate([[0], np.cumsum(sizes)])
+    idx = rng.integers(0, 500, size=ptr[-1]).astype(np.int32)
+    got = oracle.bag_sum(ptr, idx, t.astype(np.float32))
+    want = np.zeros((200, 7))
+    np.add.at(want, np.repeat(np.arange(200), sizes), t.astype(np.float32).astype(np.float64)[idx])
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-13)
+    # a bag is a graph row whose neighbours are its lookups: GIN with eps = -1 has no self term left
+    n = 200 + 500
+    rows = [idx[ptr[b]:ptr[b + 1]] + 200 for b in range(200)] + [[] for _ in range(500)]
+    row_ptr, col = inputs.csr_from_adjacency_lists([sorted(r) for r in rows])
+    x = np.concatenate([rng.standard_normal((200, 7)), t]).astype(np.float32)
+    agg = oracle.aggregate(row_ptr, col, "gin", x, eps=-1.0)[:200]
+    np.testing.assert_allclose(agg, got, rtol=1e-12, atol=1e-12)
+    # bf16 tables are read exactly
+    tb = inputs.to_bf16_bits(t.astype(np.float32))
+    np.testing.assert_allclose(oracle.bag_sum(ptr, idx, tb), oracle.bag_sum(ptr, idx, inputs.bf16_bits_to_f32(tb)), rtol=0, atol=0)
