@@ -52,9 +52,9 @@ typedef struct mgg_partition mgg_partition_t;   /* opaque, library-owned */
 /* Knobs of the partition build.  They are the paper's tuning parameters (section 6):
  * ps = neighbours per neighbour partition (1..64), dist = how many (local, remote)
  * partition pairs one wavefront work item covers (1..1024), wpb = wavefronts per workgroup
- * (the paper's warps per block).  0 selects the default
- * (ps 64 -- one neighbour id per lane of a 64-lane wavefront --, dist 8, short_max 16, xcd_min_deg 256).  Rows with at most short_max neighbours in total
- * are handled several per wavefront; short_max < 0 disables that bin. */
+ * (the paper's warps per block).  0 selects the default: ps 64 (one neighbour id per lane of a
+ * 64-lane wavefront), dist 8, short_max 16, xcd_min_deg 256.  Rows with at most short_max
+ * neighbours in total are handled several per wavefront; short_max < 0 disables that bin. */
 typedef struct {
     int32_t ps;
     int32_t dist;
