@@ -171,7 +171,8 @@ def run_tuner(cfg: int, exhaustive: bool, iters: int = 10):
     default_ms = binding.mgg_time_aggregate(part, layer.mode, xl, xh, out, eps=layer.eps, iters=iters)
     default = (int(info.ps), int(info.dist), int(info.wpb))
     part.destroy()
-    tuner = binding.Tuner(32, 16, 16)
+    # the paper's ranges, with ps up to the 64 lanes of a wavefront instead of the 32 of a warp
+    tuner = binding.Tuner(64, 16, 16)
     t0 = time.time()
     best, best_ms = binding.mgg_tune_aggregate(w.row_ptr, w.col, w.parts, w.part_id, w.bounds, layer.mode, xl, xh, out,
                                                tuner, eps=layer.eps, iters=iters)
@@ -185,7 +186,7 @@ def run_tuner(cfg: int, exhaustive: bool, iters: int = 10):
     log(f"[tune] best {best}: {best_ms:.4f} ms after {len(table)} trials (default {default}: {default_ms:.4f} ms)")
     if exhaustive:
         grid = {}
-        for ps, dist, wpb in itertools.product([1, 2, 4, 8, 16, 32], [1, 2, 4, 8, 16], [1, 2, 4, 8, 16]):
+        for ps, dist, wpb in itertools.product([1, 2, 4, 8, 16, 32, 64], [1, 2, 4, 8, 16], [1, 2, 4, 8, 16]):
             try:
                 p2 = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds, ps=ps, dist=dist, wpb=wpb)
                 grid[(ps, dist, wpb)] = binding.mgg_time_aggregate(p2, layer.mode, xl, xh, out, eps=layer.eps, iters=iters)
