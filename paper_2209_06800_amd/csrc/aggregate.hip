@@ -601,9 +601,10 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
         }
         if (slab_bytes > 0 && slab_bytes % vec_bytes == 0 && slab_bytes / vec_bytes < nvec) slab_vecs = static_cast<int>(slab_bytes / vec_bytes);
     }
+    // a lane holds at most 8 chunks of a row: wider rows are always walked in slabs of 512 vectors
+    if (slab_vecs > 64 * 8) slab_vecs = 64 * 8;
     const int n_slabs = (nvec + slab_vecs - 1) / slab_vecs;
-    // a lane holds at most 8 chunks; wider rows would need a column loop
-    if (slab_vecs > 64 * 8) return fail(MGG_ERR_UNSUPPORTED, "dim %d too wide for %d-element vectors (max %d)", dim, vec, 64 * 8 * vec);
+    if (n_slabs > 65535) return fail(MGG_ERR_UNSUPPORTED, "dim %d too wide (at most %d)", dim, 65535 * 64 * 8 * vec);
     int lpr = 4;
     while (lpr < slab_vecs && lpr < 64) lpr <<= 1;
     const int ch = (slab_vecs + 63) / 64;

@@ -105,7 +105,7 @@ def small_rmat(scale=12, draws=60000, seed=0):
 
 
 # ----------------------------------------------------------------------------- aggregation
-@pytest.mark.parametrize("dim", [1, 3, 4, 16, 20, 47, 64, 100, 128, 256, 260, 602, 608, 1024])
+@pytest.mark.parametrize("dim", [1, 3, 4, 16, 20, 47, 64, 100, 128, 256, 260, 602, 608, 1024, 2052, 4100, 601 * 3])
 @pytest.mark.parametrize("mode", ["gcn", "gin"])
 def test_aggregate_fp32_dims(dim, mode):
     row_ptr, col, rng = small_rmat(seed=dim)
