@@ -212,8 +212,8 @@ mgg_status_t mgg_bag_sum(const mgg_partition_t *p, mgg_dtype_t x_dtype, const vo
  * w_dtype F32 or BF16.  F32 weights need F32 input and use the fp32 MFMA; BF16 weights use
  * the bf16 MFMA and an F32 input is rounded to bf16 (nearest even) on the way in.
  * bias [d_out] DEVICE fp32 or NULL.  out [n_rows x d_out] DEVICE, out_dtype F32 or BF16
- * (rounded nearest even).  out must not alias a.  d_out <= 512.
- * Errors: INVALID_ARG, UNSUPPORTED (dtype combination, d_out too large), HIP.
+ * (rounded nearest even).  out must not alias a.
+ * Errors: INVALID_ARG, UNSUPPORTED (dtype combination; softmax over more than 512 columns), HIP.
  * ------------------------------------------------------------------------------------- */
 mgg_status_t mgg_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in,
                         mgg_dtype_t w_dtype, const void *w, const float *bias, int32_t d_out,
