@@ -558,11 +558,9 @@ hipError_t launch_shape(const UpdArgs &p, bool w_bf16, bool a_bf16, dim3 grid, h
 {
     if (!w_bf16 && p.w_vec_ok && p.d_out % (NT * 32 * WN) == 0 && option_update_stream() != 0) {
         constexpr int lds_bytes = 2 * 32 * NT * 32 * WN * 4;
-        static bool raised = false;     // more than 64 KB of dynamic LDS has to be asked for once
-        if (lds_bytes > 48 * 1024 && !raised) {
+        // up to 64 KB of dynamic LDS: ask for it (cheap, so done at every launch rather than remembered)
+        if (lds_bytes > 48 * 1024)
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&update_f32_db_kernel<NT, WN>), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-            raised = true;
-        }
         hipLaunchKernelGGL((update_f32_db_kernel<NT, WN>), grid, dim3(kThreads), lds_bytes, s, p);
     }
     else if (!w_bf16) hipLaunchKernelGGL((update_f32_kernel<NT, WN>), grid, dim3(kThreads), 0, s, p);
