@@ -85,6 +85,7 @@ typedef struct {
     int32_t min_piece;     /* a class with fewer neighbours than this in a row joins the row's
                               cold piece; 0 = default 16 */
     int32_t hot_min_count; /* table rows gathered fewer times than this are cold; 0 = default 8 */
+    int32_t reserve_dim;   /* > 0: the build ends with mgg_partition_reserve(p, reserve_dim) */
 } mgg_build_opts_t;
 
 typedef struct {
@@ -102,6 +103,7 @@ typedef struct {
     int64_t n_split_rows, n_split_items;      /* rows cut into > 1 item, and those items     */
     int64_t n_local_rows;                     /* rows of the local table: n_own, or the local slice of a bag partition */
     int32_t is_bags;                          /* built by mgg_build_bags                      */
+    int32_t reserved_dim;                     /* widest mgg_partition_reserve so far (0: none) */
 } mgg_partition_info_t;
 
 /* Caller-allocated HOST buffers for mgg_partition_export(); a NULL member is skipped.
@@ -148,6 +150,20 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
                                  const mgg_build_opts_t *opts, mgg_partition_t **out);
 
 mgg_status_t mgg_partition_info(const mgg_partition_t *p, mgg_partition_info_t *out);
+
+/* ---------------------------------------------------------------------------------------
+ * mgg_partition_reserve -- sizes the partition's scratch buffer for aggregations up to `dim`
+ * columns wide.  Rows with many neighbours are cut into several wavefront work items (section
+ * 4.1 Step-3: neighbour partitions; section 5.1: a wavefront takes a few of them), whose partial
+ * sums pass through this buffer: mgg_aggregate_scratch_bytes(p, dim) bytes, nothing when no row
+ * is cut.  Host, synchronous (it may wait for the device and allocate); never shrinks.  The
+ * device calls below allocate nothing: mgg_aggregate / mgg_aggregate_to / mgg_bag_sum /
+ * mgg_time_aggregate on a width that was not reserved fail with MGG_ERR_INVALID_ARG.
+ * mgg_layer_forward does not use this buffer (its workspace holds the partial sums).
+ * Errors: INVALID_ARG, ALLOC, HIP.
+ * ------------------------------------------------------------------------------------- */
+mgg_status_t mgg_partition_reserve(mgg_partition_t *p, int32_t dim);
+size_t       mgg_aggregate_scratch_bytes(const mgg_partition_t *p, int32_t dim);   /* 0 on bad arguments */
 mgg_status_t mgg_partition_export(const mgg_partition_t *p, mgg_partition_arrays_t *host_buffers);
 void         mgg_partition_destroy(mgg_partition_t *p);   /* NULL is allowed */
 
@@ -166,9 +182,9 @@ void         mgg_partition_destroy(mgg_partition_t *p);   /* NULL is allowed */
  * padding holds is never used), so that a width like 602 or 47 still gets 16-byte loads.
  * out [n_own x dim] is DEVICE fp32, ld_out >= dim, fully overwritten (columns >= dim of a
  * padded out are not touched); it must not alias the inputs.  Accumulation is fp32.
- * The first call with a larger dim than any before grows the partition's scratch buffer
- * (a synchronising device allocation); later calls allocate nothing.
- * Errors: INVALID_ARG (NULL, dim < 1, ld < dim, host-only partition), HIP, ALLOC.
+ * Allocates nothing and never synchronises: the width must have been reserved
+ * (mgg_partition_reserve, or reserve_dim at build) when the partition cuts rows into several items.
+ * Errors: INVALID_ARG (NULL, dim < 1, ld < dim, host-only partition, width not reserved), HIP.
  * ------------------------------------------------------------------------------------- */
 mgg_status_t mgg_aggregate(const mgg_partition_t *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
                            const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x,
@@ -254,8 +270,9 @@ typedef struct {
     mgg_order_t order;         /* 0 = AGG_FIRST, the paper's formulation */
 } mgg_layer_desc_t;
 
-/* Bytes of DEVICE workspace mgg_layer_forward needs (aggregation result and, for two
- * linears, the hidden activations; with UPDATE_FIRST the transformed local and halo tables).
+/* Bytes of DEVICE workspace mgg_layer_forward needs (aggregation result, the partial sums of rows
+ * cut into several work items and, for two linears, the hidden activations; with UPDATE_FIRST the
+ * transformed local and halo tables).
  * Returns 0 on bad arguments. */
 size_t mgg_layer_workspace_bytes(const mgg_partition_t *p, const mgg_layer_desc_t *layer);
 
@@ -341,6 +358,8 @@ mgg_status_t mgg_tune_aggregate(int64_t num_nodes, const int64_t *row_ptr, const
  *                      0 = the plain register-resident and slab kernels everywhere)
  *   "col_slab_bytes"   0 = automatic (default), 1 = off, or a power of two in [64, 4096]:
  *                      bytes of an embedding row handled per pass over the work items
+ *   "items_per_wave"   0 = automatic (default), or 1..64: work items a wavefront takes one after
+ *                      the other, the next one's ids and descriptor requested while it gathers
  * Unknown key or bad value -> MGG_ERR_INVALID_ARG.  Not thread-safe against running calls. */
 mgg_status_t mgg_set_option(const char *key, int32_t value);
 mgg_status_t mgg_get_option(const char *key, int32_t *value);

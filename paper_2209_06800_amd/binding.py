@@ -27,7 +27,7 @@ _STATUS_NAME = ["OK", "INVALID_ARG", "BAD_GRAPH", "UNSUPPORTED", "ALLOC", "HIP"]
 
 EXPORTED_SYMBOLS = [
     "mgg_build_partition", "mgg_partition_info", "mgg_partition_export", "mgg_partition_destroy",
-    "mgg_aggregate", "mgg_aggregate_to", "mgg_build_bags", "mgg_bag_sum", "mgg_update", "mgg_update_mlp", "mgg_layer_workspace_bytes", "mgg_layer_forward",
+    "mgg_partition_reserve", "mgg_aggregate_scratch_bytes", "mgg_aggregate", "mgg_aggregate_to", "mgg_build_bags", "mgg_bag_sum", "mgg_update", "mgg_update_mlp", "mgg_layer_workspace_bytes", "mgg_layer_forward",
     "mgg_split_edge_balanced", "mgg_set_option", "mgg_get_option", "mgg_time_aggregate",
     "mgg_model_evaluate", "mgg_tuner_create", "mgg_tuner_next", "mgg_tuner_report", "mgg_tuner_result",
     "mgg_tuner_table", "mgg_tuner_destroy", "mgg_tune_aggregate",
@@ -44,7 +44,7 @@ class MggError(RuntimeError):
 class BuildOpts(C.Structure):
     _fields_ = [("ps", C.c_int32), ("dist", C.c_int32), ("short_max", C.c_int32), ("host_only", C.c_int32),
                 ("wpb", C.c_int32), ("xcd_min_deg", C.c_int32), ("hot_row_bytes", C.c_int32), ("hot_rows", C.c_int32),
-                ("hot_phases", C.c_int32), ("min_piece", C.c_int32), ("hot_min_count", C.c_int32)]
+                ("hot_phases", C.c_int32), ("min_piece", C.c_int32), ("hot_min_count", C.c_int32), ("reserve_dim", C.c_int32)]
 
 
 class PartitionInfo(C.Structure):
@@ -58,7 +58,7 @@ class PartitionInfo(C.Structure):
                 ("n_groups_local", C.c_int64), ("n_groups_remote", C.c_int64),
                 ("n_short_rows", C.c_int64), ("n_items", C.c_int64),
                 ("n_split_rows", C.c_int64), ("n_split_items", C.c_int64),
-                ("n_local_rows", C.c_int64), ("is_bags", C.c_int32)]
+                ("n_local_rows", C.c_int64), ("is_bags", C.c_int32), ("reserved_dim", C.c_int32)]
 
 
 _ARRAY_FIELDS = ["local_row_ptr", "local_col", "remote_row_ptr", "remote_col", "halo_gid", "halo_peer_ptr",
@@ -113,6 +113,9 @@ def lib():
         L.mgg_partition_export.argtypes = [C.c_void_p, C.POINTER(PartitionArrays)]
         L.mgg_aggregate.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_int32,
                                     C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
+        L.mgg_partition_reserve.argtypes = [C.c_void_p, C.c_int32]
+        L.mgg_aggregate_scratch_bytes.restype = C.c_size_t
+        L.mgg_aggregate_scratch_bytes.argtypes = [C.c_void_p, C.c_int32]
         L.mgg_aggregate_to.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_int32,
                                        C.c_int64, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
         L.mgg_build_bags.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p,
@@ -203,6 +206,7 @@ class Partition:
         self._h = C.c_void_p(handle)
         self.info = PartitionInfo()
         _check(lib().mgg_partition_info(self._h, C.byref(self.info)))
+        self._reserved = int(self.info.reserved_dim)
 
     @property
     def handle(self):
@@ -220,6 +224,12 @@ class Partition:
             self.destroy()
         except Exception:
             pass
+
+    def reserve(self, dim: int):
+        """mgg_partition_reserve: size the partition's scratch buffer for aggregations up to `dim` wide."""
+        if dim > self._reserved:
+            _check(lib().mgg_partition_reserve(self.handle, int(dim)))
+            self._reserved = int(dim)
 
     def export(self) -> dict:
         """Copy every integer structure to numpy arrays (for bit-exact checks)."""
@@ -247,7 +257,7 @@ def mgg_build_partition(row_ptr: np.ndarray, col_idx: np.ndarray, num_parts: int
                         bounds: Optional[Sequence[int]] = None, *, ps: int = 0, dist: int = 0,
                         short_max: int = 0, host_only: bool = False, xcd_min_deg: int = 0, wpb: int = 0,
                         hot_row_bytes: int = 0, hot_rows: int = 0, hot_phases: int = 0, min_piece: int = 0,
-                        hot_min_count: int = 0, num_nodes: Optional[int] = None) -> Partition:
+                        hot_min_count: int = 0, reserve_dim: int = 0, num_nodes: Optional[int] = None) -> Partition:
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
     n = row_ptr.size - 1 if num_nodes is None else num_nodes
@@ -255,7 +265,7 @@ def mgg_build_partition(row_ptr: np.ndarray, col_idx: np.ndarray, num_parts: int
     if b is not None and b.size != num_parts + 1:
         raise MggError(ERR_INVALID_ARG, "bounds must have num_parts + 1 entries")
     opts = BuildOpts(ps, dist, short_max, int(host_only), wpb, xcd_min_deg, hot_row_bytes, hot_rows, hot_phases,
-                     min_piece, hot_min_count)
+                     min_piece, hot_min_count, reserve_dim)
     h = C.c_void_p()
     _check(lib().mgg_build_partition(n, _np_ptr(row_ptr), _np_ptr(col_idx) if col_idx.size else None,
                                      num_parts, part_id, _np_ptr(b), C.byref(opts), C.byref(h)))
@@ -284,6 +294,8 @@ def mgg_bag_sum(part: Partition, table_local, table_halo=None, *, out=None, out_
     dim = int(ref.shape[1]) if dim is None else dim
     if out is None:
         out = torch.empty((int(part.info.n_own), dim), dtype=out_dtype or torch.float32, device=ref.device)
+    _check_tables(part, table_local, table_halo, out, dim, bags=True)
+    part.reserve(dim)
     _check(lib().mgg_bag_sum(part.handle, _torch_dtype_code(ref), _dev_ptr(table_local), _dev_ptr(table_halo), dim, _ld(ref),
                              _torch_dtype_code(out), _dev_ptr(out), _ld(out), _stream(stream)))
     return out
@@ -307,6 +319,39 @@ def mgg_get_option(key: str) -> int:
 
 
 # ------------------------------------------------------------------------------- device calls
+def _check_tables(part: Partition, x_local, x_halo, out, dim: int, bags: bool = False):
+    """The C ABI takes bare pointers and one leading dimension for both tables; what it cannot see is
+    checked here: both tables of one dtype, device and row stride, and every buffer long enough."""
+    i = part.info
+    if bool(i.is_bags) != bags:
+        return                      # the wrong kind of partition for this call: the library says so
+    n_local = int(i.n_local_rows) if bags else int(i.n_own)
+    ref = x_local if x_local is not None else x_halo
+    if ref is None:
+        if n_local or int(i.num_halo):
+            raise ValueError("no embedding table given")
+        return
+    if x_local is not None and x_halo is not None:
+        if x_halo.dtype != x_local.dtype or x_halo.device != x_local.device:
+            raise ValueError(f"x_halo is {x_halo.dtype} on {x_halo.device}, x_local is {x_local.dtype} on {x_local.device}")
+        if int(x_halo.shape[0]) > 0 and int(x_local.shape[0]) > 0 and _ld(x_halo) != _ld(x_local):
+            raise ValueError(f"x_halo has row stride {_ld(x_halo)}, x_local {_ld(x_local)}: the library takes one ld_x for both tables")
+    for name, t, rows in (("x_local", x_local, n_local), ("x_halo", x_halo, int(i.num_halo))):
+        if t is None:
+            continue
+        if t.dim() != 2 or int(t.shape[1]) < dim:
+            raise ValueError(f"{name} must be 2-D with at least {dim} columns, got {tuple(t.shape)}")
+        if int(t.shape[0]) < rows:
+            raise ValueError(f"{name} has {int(t.shape[0])} rows, the partition needs {rows}")
+    if x_halo is None and int(i.num_halo) > 0 and not bags:
+        raise ValueError(f"x_halo is missing: the partition has {int(i.num_halo)} halo rows")
+    if out is not None:
+        if out.dim() != 2 or int(out.shape[0]) < int(i.n_own) or int(out.shape[1]) < dim:
+            raise ValueError(f"out must hold at least {int(i.n_own)} x {dim}, got {tuple(out.shape)}")
+        if out.device != ref.device:
+            raise ValueError("out lives on another device than the tables")
+
+
 def mgg_aggregate(part: Partition, mode: str, x_local, x_halo=None, *, eps: float = 0.0, out=None,
                   dim: Optional[int] = None, stream=None, out_dtype=None):
     """out[n_own x dim] = Aggregate over N(v) U {v}; fp32, or bf16 (mgg_aggregate_to) when `out` or
@@ -315,6 +360,8 @@ def mgg_aggregate(part: Partition, mode: str, x_local, x_halo=None, *, eps: floa
     dim = int(x_local.shape[1]) if dim is None else dim
     if out is None:
         out = torch.empty((int(part.info.n_own), dim), dtype=out_dtype or torch.float32, device=x_local.device)
+    _check_tables(part, x_local, x_halo, out, dim)
+    part.reserve(dim)          # the C call allocates nothing; sizing the scratch buffer is a call of its own
     if out.dtype == torch.float32:
         _check(lib().mgg_aggregate(part.handle, _MODE[mode], eps, _torch_dtype_code(x_local), _dev_ptr(x_local),
                                    _dev_ptr(x_halo), dim, _ld(x_local), _dev_ptr(out), _ld(out), _stream(stream)))
@@ -325,10 +372,16 @@ def mgg_aggregate(part: Partition, mode: str, x_local, x_halo=None, *, eps: floa
     return out
 
 
+def mgg_aggregate_scratch_bytes(part: Partition, dim: int) -> int:
+    return int(lib().mgg_aggregate_scratch_bytes(part.handle, int(dim)))
+
+
 def mgg_time_aggregate(part: Partition, mode: str, x_local, x_halo, out, *, eps: float = 0.0, iters: int = 20,
                        dim: Optional[int] = None, stream=None) -> float:
     """Mean milliseconds per mgg_aggregate call, HIP events on the launch stream."""
     dim = int(x_local.shape[1]) if dim is None else dim
+    _check_tables(part, x_local, x_halo, out, dim)
+    part.reserve(dim)
     ms = C.c_float()
     _check(lib().mgg_time_aggregate(part.handle, _MODE[mode], eps, _torch_dtype_code(x_local), _dev_ptr(x_local),
                                     _dev_ptr(x_halo), dim, _ld(x_local), _dev_ptr(out), _ld(out), _stream(stream),
@@ -406,6 +459,9 @@ def mgg_layer_forward(part: Partition, mode: str, x_local, x_halo, weights, acts
     if out is None:
         out = torch.empty((int(part.info.n_own), int(weights[-1].shape[1])), dtype=out_dtype or torch.float32,
                           device=x_local.device)
+    _check_tables(part, x_local, x_halo, None, int(weights[0].shape[0]))
+    if int(out.shape[0]) < int(part.info.n_own) or int(out.shape[1]) < int(weights[-1].shape[1]):
+        raise ValueError(f"out must hold at least {int(part.info.n_own)} x {int(weights[-1].shape[1])}, got {tuple(out.shape)}")
     _check(lib().mgg_layer_forward(part.handle, C.byref(d), _torch_dtype_code(x_local), _dev_ptr(x_local),
                                    _dev_ptr(x_halo), _ld(x_local), _dev_ptr(workspace), workspace.numel(),
                                    _torch_dtype_code(out), _dev_ptr(out), _ld(out), _stream(stream)))

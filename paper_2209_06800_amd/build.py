@@ -16,7 +16,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmgg.so")
 
-SOURCES = ["partition.cpp", "api.cpp", "tuner.cpp", "aggregate.hip", "update.hip", "update_stream.hip"]
+SOURCES = ["partition.cpp", "api.cpp", "tuner.cpp", "aggregate.hip", "aggregate_f32.hip", "aggregate_bf16.hip", "update.hip",
+           "update_stream.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -11,10 +11,12 @@ static std::atomic<int32_t> g_lds_halo{0};
 static std::atomic<int32_t> g_col_slab_bytes{0};
 static std::atomic<int32_t> g_split_phases{0};
 static std::atomic<int32_t> g_update_stream{1};
+static std::atomic<int32_t> g_items_per_wave{0};
 int32_t option_lds_halo() { return g_lds_halo.load(); }
 int32_t option_col_slab_bytes() { return g_col_slab_bytes.load(); }
 int32_t option_split_phases() { return g_split_phases.load(); }
 int32_t option_update_stream() { return g_update_stream.load(); }
+int32_t option_items_per_wave() { return g_items_per_wave.load(); }
 
 static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline bool dtype_ok(mgg_dtype_t t) { return t == MGG_F32 || t == MGG_BF16; }
@@ -64,8 +66,10 @@ struct LayerPlan {
     int64_t ld_agg = 0, ld_hid = 0;
     size_t agg_bytes = 0, hid_bytes = 0;        // aggregation result (width dims[0], or dims[1] when update_first), hidden activations
     size_t t_local_bytes = 0, t_halo_bytes = 0; // update_first: X w[0] of the two tables, leading dimension ld_agg
+    size_t scratch_bytes = 0;                   // partial sums of rows cut into several work items (last in the workspace)
     mgg_dtype_t hid_dtype = MGG_F32;
-    size_t total() const { return agg_bytes + hid_bytes + t_local_bytes + t_halo_bytes; }
+    size_t total() const { return agg_bytes + hid_bytes + t_local_bytes + t_halo_bytes + scratch_bytes; }
+    size_t scratch_offset() const { return agg_bytes + hid_bytes + t_local_bytes + t_halo_bytes; }
 };
 
 static bool plan_layer(const mgg_partition *p, const mgg_layer_desc_t *l, mgg_dtype_t x_dtype, mgg_dtype_t out_dtype, LayerPlan *pl)
@@ -87,6 +91,7 @@ static bool plan_layer(const mgg_partition *p, const mgg_layer_desc_t *l, mgg_dt
         pl->t_halo_bytes = round_up(p->halo_gid.size() * static_cast<size_t>(pl->ld_agg) * sizeof(float), 256);
         if (l->n_linear == 1) pl->agg_bytes = 0;       // aggregated rows are the layer's output
     }
+    pl->scratch_bytes = round_up(scratch_bytes_for(p, static_cast<int32_t>(pl->ld_agg)), 256);
     if (l->n_linear == 2 && !pl->update_first) {
         pl->hid_dtype = l->w_dtype == MGG_BF16 ? MGG_BF16 : MGG_F32;
         pl->ld_hid = static_cast<int64_t>(round_up(static_cast<size_t>(l->dims[1]), 8));
@@ -120,6 +125,33 @@ mgg_status_t mgg_aggregate_to(const mgg_partition_t *p, mgg_agg_t mode, float ep
     if (p->n_own == 0) return MGG_OK;
     return launch_aggregate(p, mode, eps, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out, static_cast<hipStream_t>(stream), nullptr,
                             MGG_ACT_NONE, 0, out_dtype);
+}
+
+size_t mgg_aggregate_scratch_bytes(const mgg_partition_t *p, int32_t dim)
+{
+    if (!p || dim < 1) return 0;
+    return scratch_bytes_for(p, dim);
+}
+
+mgg_status_t mgg_partition_reserve(mgg_partition_t *p, int32_t dim)
+{
+    if (!p) return fail(MGG_ERR_INVALID_ARG, "partition is NULL");
+    if (p->device < 0) return fail(MGG_ERR_INVALID_ARG, "partition was built host-only");
+    if (dim < 1) return fail(MGG_ERR_INVALID_ARG, "dim %d", dim);
+    int dev = -1;
+    MGG_HIP_TRY(hipGetDevice(&dev));
+    if (dev != p->device) return fail(MGG_ERR_INVALID_ARG, "partition lives on device %d, current device is %d", p->device, dev);
+    const int64_t need_ld = scratch_ld_for(dim);
+    if (p->reserved_dim < dim) p->reserved_dim = dim;
+    if (p->n_split_items == 0 || p->d.scratch_ld >= need_ld) return MGG_OK;
+    // work already enqueued may still use the old buffer
+    MGG_HIP_TRY(hipDeviceSynchronize());
+    if (p->d.scratch) { (void)hipFree(p->d.scratch); p->d.scratch = nullptr; p->d.scratch_ld = 0; }
+    const size_t bytes = static_cast<size_t>(p->n_split_items) * static_cast<size_t>(need_ld) * sizeof(float);
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&p->d.scratch), bytes);
+    if (e != hipSuccess) { p->reserved_dim = 0; return fail(MGG_ERR_ALLOC, "hipMalloc(%zu bytes of scratch): %s", bytes, hipGetErrorString(e)); }
+    p->d.scratch_ld = need_ld;
+    return MGG_OK;
 }
 
 mgg_status_t mgg_bag_sum(const mgg_partition_t *p, mgg_dtype_t x_dtype, const void *table_local, const void *table_halo, int32_t dim,
@@ -203,7 +235,8 @@ mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t 
         const int32_t d1_padded = static_cast<int32_t>(std::min<int64_t>(round_up(static_cast<size_t>(d1), 4), pl.ld_agg));
         const bool softmax0 = layer->act[0] == MGG_ACT_SOFTMAX;     // not an elementwise epilogue: its own pass
         s = launch_aggregate(p, layer->mode, layer->eps, MGG_F32, t_local, n_halo > 0 ? t_halo : nullptr, d1_padded, pl.ld_agg, agg,
-                             ld_aggout, st, layer->bias[0], softmax0 ? MGG_ACT_NONE : layer->act[0], d1);
+                             ld_aggout, st, layer->bias[0], softmax0 ? MGG_ACT_NONE : layer->act[0], d1, MGG_F32,
+                             reinterpret_cast<float *>(ws + pl.scratch_offset()), pl.scratch_bytes);
         if (s == MGG_OK && softmax0) s = launch_row_softmax(p->n_own, d1, MGG_F32, agg, ld_aggout, st);
         if (s != MGG_OK || layer->n_linear == 1) return s;
         return launch_update(p->n_own, MGG_F32, agg, pl.ld_agg, d1, layer->w_dtype, layer->w[1], layer->bias[1], d2, layer->act[1],
@@ -228,7 +261,8 @@ mgg_status_t mgg_layer_forward(const mgg_partition_t *p, const mgg_layer_desc_t 
     if (s != MGG_OK) return s;
     if (p->n_own == 0) return MGG_OK;
 
-    s = launch_aggregate(p, layer->mode, layer->eps, x_dtype, x_local, x_halo, d0, ld_x, agg, pl.ld_agg, st, nullptr, MGG_ACT_NONE, 0, agg_dtype);
+    s = launch_aggregate(p, layer->mode, layer->eps, x_dtype, x_local, x_halo, d0, ld_x, agg, pl.ld_agg, st, nullptr, MGG_ACT_NONE, 0, agg_dtype,
+                         reinterpret_cast<float *>(static_cast<char *>(workspace) + pl.scratch_offset()), pl.scratch_bytes);
     if (s != MGG_OK) return s;
     if (layer->n_linear == 1)
         return launch_update(p->n_own, agg_dtype, agg, pl.ld_agg, d0, layer->w_dtype, layer->w[0], layer->bias[0], d1,
@@ -264,6 +298,11 @@ mgg_status_t mgg_set_option(const char *key, int32_t value)
         g_col_slab_bytes = value;
         return MGG_OK;
     }
+    if (!std::strcmp(key, "items_per_wave")) {
+        if (value < 0 || value > 64) return fail(MGG_ERR_INVALID_ARG, "items_per_wave must be 0 (automatic) or 1..64");
+        g_items_per_wave = value;
+        return MGG_OK;
+    }
     if (value != 0 && value != 1) return fail(MGG_ERR_INVALID_ARG, "option value must be 0 or 1");
     if (!std::strcmp(key, "lds_halo")) { g_lds_halo = value; return MGG_OK; }
     if (!std::strcmp(key, "split_phases")) { g_split_phases = value; return MGG_OK; }
@@ -278,6 +317,7 @@ mgg_status_t mgg_get_option(const char *key, int32_t *value)
     if (!std::strcmp(key, "col_slab_bytes")) { *value = g_col_slab_bytes; return MGG_OK; }
     if (!std::strcmp(key, "split_phases")) { *value = g_split_phases; return MGG_OK; }
     if (!std::strcmp(key, "update_stream")) { *value = g_update_stream; return MGG_OK; }
+    if (!std::strcmp(key, "items_per_wave")) { *value = g_items_per_wave; return MGG_OK; }
     return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
 }
 
@@ -287,7 +327,7 @@ mgg_status_t mgg_time_aggregate(const mgg_partition_t *p, mgg_agg_t mode, float 
 {
     if (iters < 1 || !ms_per_call) return fail(MGG_ERR_INVALID_ARG, "iters < 1 or ms_per_call is NULL");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // one untimed call first: it validates the arguments and grows the scratch buffer if needed
+    // one untimed call first: it validates the arguments
     mgg_status_t s = mgg_aggregate(p, mode, eps, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out, stream);
     if (s != MGG_OK) return s;
     hipEvent_t e0 = nullptr, e1 = nullptr;

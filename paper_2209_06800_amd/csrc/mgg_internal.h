@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime_api.h>
+#include <hip/hip_vector_types.h>
 
 #include <cstdarg>
 #include <cstdint>
@@ -49,7 +50,7 @@ struct DeviceArrays {
     int32_t *remote_row_ptr = nullptr, *remote_col = nullptr;
     float *dinv_own = nullptr;
     float *w_local = nullptr, *w_remote = nullptr;   // 1/sqrt(deg+1) of the neighbour, per entry of the column arrays
-    int32_t *short_rows = nullptr;
+    int4 *short_desc = nullptr;        // per short row: row, start in local_col, start in remote_col, counts (local | remote << 16)
     WorkItem *items = nullptr;
     SplitRow *split_rows = nullptr;
     float *scratch = nullptr;          // [n_split_items x scratch_ld] partial sums
@@ -77,8 +78,9 @@ struct mgg_partition {
     std::vector<mgg::WorkItem> items;
     std::vector<mgg::SplitRow> split_rows;
     int64_t n_split_items = 0;
+    int32_t reserved_dim = 0;         // widest aggregation the partition's own scratch buffer was sized for
     int64_t n_groups_local = 0, n_groups_remote = 0;
-    mutable mgg::DeviceArrays d;  // scratch grows lazily inside const calls
+    mgg::DeviceArrays d;          // device copies; d.scratch is sized by mgg_partition_reserve (or at build)
 };
 
 namespace mgg {
@@ -96,12 +98,18 @@ int32_t option_lds_halo();
 int32_t option_col_slab_bytes();
 int32_t option_split_phases();
 int32_t option_update_stream();
+int32_t option_items_per_wave();
 
 // kernels (aggregate.hip / update.hip)
 mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
                               const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x,
                               void *out, int64_t ld_out, hipStream_t stream, const float *bias = nullptr,
-                              mgg_act_t act = MGG_ACT_NONE, int32_t out_dim = 0, mgg_dtype_t out_dtype = MGG_F32);
+                              mgg_act_t act = MGG_ACT_NONE, int32_t out_dim = 0, mgg_dtype_t out_dtype = MGG_F32,
+                              float *scratch = nullptr, size_t scratch_bytes = 0);
+// scratch / scratch_bytes: where the partial sums of rows cut into several items go; NULL = the partition's
+// own buffer (mgg_partition_reserve).  The launch allocates nothing: too small a buffer is an error.
+inline int64_t scratch_ld_for(int32_t dim) { return (static_cast<int64_t>(dim) + 7) / 8 * 8; }   // rows of partial sums start on 32-byte boundaries
+inline size_t scratch_bytes_for(const mgg_partition *p, int32_t dim) { return static_cast<size_t>(p->n_split_items) * static_cast<size_t>(scratch_ld_for(dim)) * sizeof(float); }
 // bias / act: optional epilogue of the final value.  out_dim (0 = dim): columns of `out` that exist
 // when the tables carry padding columns beyond them (dim counts the padded width).  out_dtype BF16: the
 // rows are rounded to bf16 (nearest even) on the way out -- what the bf16 MFMA would do on the way in.

@@ -46,7 +46,7 @@ static void free_device(mgg_partition *p)
     if (p->device < 0) return;
     DeviceArrays &d = p->d;
     void *ptrs[] = {d.local_row_ptr, d.local_col, d.remote_row_ptr, d.remote_col, d.dinv_own, d.w_local,
-                    d.w_remote,      d.short_rows, d.items,         d.split_rows, d.scratch};
+                    d.w_remote,      d.short_desc, d.items,         d.split_rows, d.scratch};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
     d = DeviceArrays{};
@@ -75,7 +75,16 @@ static mgg_status_t upload_all(mgg_partition *p)
         for (size_t i = 0; i < w.size(); ++i) w[i] = p->dinv_halo[rc[i]];
         if ((s = upload(w, &p->d.w_remote)) != MGG_OK) return s;
     }
-    if ((s = upload(p->short_rows, &p->d.short_rows)) != MGG_OK) return s;
+    {
+        // one 16-byte record per short row, so that the kernel needs no dependent look-up of row pointers
+        std::vector<int4> sd(p->short_rows.size());
+        for (size_t i = 0; i < sd.size(); ++i) {
+            const int32_t v = p->short_rows[i];
+            const int32_t nl = p->local_row_ptr[v + 1] - p->local_row_ptr[v], nr = p->remote_row_ptr[v + 1] - p->remote_row_ptr[v];
+            sd[i] = make_int4(v, p->local_row_ptr[v], p->remote_row_ptr[v], nl | (nr << 16));
+        }
+        if ((s = upload(sd, &p->d.short_desc)) != MGG_OK) return s;
+    }
     if ((s = upload(p->items, &p->d.items)) != MGG_OK) return s;
     if ((s = upload(p->split_rows, &p->d.split_rows)) != MGG_OK) return s;
     return MGG_OK;
@@ -109,6 +118,7 @@ static void copy_out(const std::vector<T> &v, T *dst)
 struct Knobs {
     int32_t ps = 64, dist = 8, short_max = 16, host_only = 0, xcd_min_deg = kDefaultXcdMinDeg, wpb = kDefaultWpb;
     int32_t hot_rows = 0, hot_phases = kDefaultHotPhases, min_piece = kDefaultMinPiece, hot_min_count = kDefaultHotMinCount;
+    int32_t reserve_dim = 0;
 };
 
 static mgg_status_t parse_opts(const mgg_build_opts_t *opts, Knobs *k)
@@ -128,6 +138,7 @@ static mgg_status_t parse_opts(const mgg_build_opts_t *opts, Knobs *k)
         host_only = opts->host_only;
         if (opts->xcd_min_deg) xcd_min_deg = opts->xcd_min_deg;
         if (opts->wpb) wpb = opts->wpb;
+        k->reserve_dim = opts->reserve_dim;
     }
     if (ps < 1 || ps > 64) return fail(MGG_ERR_INVALID_ARG, "ps %d outside [1, 64]", ps);
     if (dist < 1 || dist > 1024) return fail(MGG_ERR_INVALID_ARG, "dist %d outside [1, 1024]", dist);
@@ -143,6 +154,7 @@ static mgg_status_t parse_opts(const mgg_build_opts_t *opts, Knobs *k)
     if (hot_phases > kMaxHotPhases) return fail(MGG_ERR_INVALID_ARG, "hot_phases %d above %d", hot_phases, kMaxHotPhases);
     if (min_piece < 1) return fail(MGG_ERR_INVALID_ARG, "min_piece %d below 1", min_piece);
     if (hot_min_count < 1) return fail(MGG_ERR_INVALID_ARG, "hot_min_count %d below 1", hot_min_count);
+    if (k->reserve_dim < 0) return fail(MGG_ERR_INVALID_ARG, "reserve_dim %d below 0", k->reserve_dim);
     return MGG_OK;
 }
 
@@ -446,6 +458,7 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
 
     if (!host_only) {
         mgg_status_t s = upload_all(p);
+        if (s == MGG_OK && knobs.reserve_dim > 0) s = mgg_partition_reserve(p, knobs.reserve_dim);
         if (s != MGG_OK) { free_device(p); delete p; return s; }
     }
     *out = p;
@@ -513,6 +526,7 @@ mgg_status_t mgg_build_bags(int64_t num_bags, const int64_t *bag_ptr, const int3
     }
     if (!knobs.host_only) {
         mgg_status_t s = upload_all(p);
+        if (s == MGG_OK && knobs.reserve_dim > 0) s = mgg_partition_reserve(p, knobs.reserve_dim);
         if (s != MGG_OK) { free_device(p); delete p; return s; }
     }
     *out = p;
@@ -538,6 +552,7 @@ mgg_status_t mgg_partition_info(const mgg_partition_t *p, mgg_partition_info_t *
     o->n_items = static_cast<int64_t>(p->items.size());
     o->n_split_rows = static_cast<int64_t>(p->split_rows.size());
     o->n_split_items = p->n_split_items;
+    o->reserved_dim = p->reserved_dim;
     return MGG_OK;
 }
 

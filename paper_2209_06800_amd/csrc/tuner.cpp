@@ -190,7 +190,8 @@ mgg_status_t mgg_tune_aggregate(int64_t num_nodes, const int64_t *row_ptr, const
         s = mgg_build_partition(num_nodes, row_ptr, col_idx, num_parts, part_id, bounds, &o, &p);
         float ms = 0.f;
         if (s == MGG_OK) {
-            s = mgg_time_aggregate(p, mode, eps, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out, stream, iters, &ms);
+            s = mgg_partition_reserve(p, dim);
+            if (s == MGG_OK) s = mgg_time_aggregate(p, mode, eps, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out, stream, iters, &ms);
             mgg_partition_destroy(p);
         }
         double latency = static_cast<double>(ms);

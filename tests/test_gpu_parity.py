@@ -674,11 +674,75 @@ def test_aggregate_random_graphs_and_schedules(seed):
 
 
 # ----------------------------------------------------------------------------- HIP graph capture
+def test_layer_forward_captured_without_any_eager_call():
+    """A layer forward takes everything it needs from its arguments (the partial sums of cut rows pass
+    through the workspace): the very first call on a fresh partition can be the one that is captured,
+    at a width no earlier call ever used."""
+    w = inputs.config(5, shrink=5)
+    part = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
+    assert part.info.n_split_items > 0 and part.info.reserved_dim == 0
+    hg = part.export()["halo_gid"]
+    rng = np.random.default_rng(11)
+    dims = (328, 72)                                     # wider than anything this partition has seen (nothing)
+    x = rng.standard_normal((w.row_ptr.size - 1, dims[0])).astype(np.float32)
+    wt = (0.1 * rng.standard_normal(dims)).astype(np.float32)
+    xl, xh, dw = to_dev(x[w.lb:w.ub]), to_dev(x[hg]), [to_dev(wt)]
+    wsp = torch.empty(binding.mgg_layer_workspace_bytes(part, "gcn", dw, ["relu"]), dtype=torch.uint8, device=DEV)
+    out = torch.full((int(part.info.n_own), dims[1]), float("nan"), device=DEV)
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        binding.mgg_layer_forward(part, "gcn", xl, xh, dw, ["relu"], workspace=wsp, out=out)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        out.fill_(float("nan"))
+        wsp.random_(0, 255)                              # whatever the workspace held must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = to_host64(out)
+        ref = oracle.layer_forward(w.row_ptr, w.col, "gcn", x[w.lb:w.ub], [wt], ["relu"], lb=w.lb, ub=w.ub, x_halo=x[hg], halo_gid=hg)
+        agg = oracle.aggregate(w.row_ptr, w.col, "gcn", x[w.lb:w.ub], lb=w.lb, ub=w.ub, x_halo=x[hg], halo_gid=hg)
+        s = np.abs(agg) @ np.abs(wt).astype(np.float64)
+        assert_close(got, ref, 1e-4, 2e-6 * s + 2.0 * dims[0] * 2.0 ** -24 * s, f"captured layer, replay {rep}")
+    info = binding.PartitionInfo()
+    import ctypes
+    binding.lib().mgg_partition_info(part.handle, ctypes.byref(info))
+    assert info.reserved_dim == 0
+    part.destroy()
+
+
+def test_aggregate_refuses_a_width_that_was_not_reserved():
+    """mgg_aggregate allocates nothing: on a partition that cuts rows into several items the width has to
+    be reserved first (the Python binding does that on its own; the raw call is made here)."""
+    import ctypes
+    w = inputs.config(2, shrink=5)
+    part = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds, reserve_dim=32)
+    assert part.info.n_split_items > 0 and part.info.reserved_dim == 32
+    hg = part.export()["halo_gid"]
+    xl, xh = to_dev(w.x[w.lb:w.ub]), to_dev(w.x[hg])
+    out = torch.full((int(part.info.n_own), w.dim), 3.0, device=DEV)
+    lib = binding.lib()
+    args = (part.handle, binding.AGG_GCN_SYM, ctypes.c_float(0.0), binding.F32, ctypes.c_void_p(xl.data_ptr()), ctypes.c_void_p(xh.data_ptr()))
+    st = lib.mgg_aggregate(*args, w.dim, w.dim, ctypes.c_void_p(out.data_ptr()), w.dim, None)
+    assert st == binding.ERR_INVALID_ARG and b"mgg_partition_reserve" in lib.mgg_last_error()
+    torch.cuda.synchronize()
+    assert bool((out == 3.0).all())
+    st = lib.mgg_aggregate(*args, 32, w.dim, ctypes.c_void_p(out.data_ptr()), w.dim, None)      # the reserved width works
+    assert st == binding.OK
+    assert lib.mgg_partition_reserve(part.handle, w.dim) == binding.OK
+    st = lib.mgg_aggregate(*args, w.dim, w.dim, ctypes.c_void_p(out.data_ptr()), w.dim, None)
+    assert st == binding.OK
+    torch.cuda.synchronize()
+    want = binding.mgg_aggregate(part, "gcn", xl, xh)
+    assert torch.equal(out, want)
+    part.destroy()
+
+
 def test_layer_forward_in_a_hip_graph():
-    """After one eager call (which sizes the partition's scratch buffer) a layer forward allocates
-    nothing, synchronises nothing and records no memset, so it can be captured in a HIP graph.  Every
-    replay -- with new inputs, and with eager work and synchronisations in between -- must reproduce
-    the eager result bit for bit."""
+    """A layer forward allocates nothing, synchronises nothing and records no memset, so it can be
+    captured in a HIP graph.  Every replay -- with new inputs, and with eager work and
+    synchronisations in between -- must reproduce the eager result bit for bit."""
     w = inputs.config(2, shrink=5)
     part = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
     hg = part.export()["halo_gid"]
@@ -694,7 +758,7 @@ def test_layer_forward_in_a_hip_graph():
 
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
-        forward()                                   # eager: grows the scratch buffer
+        forward()
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=stream):

@@ -268,7 +268,56 @@ def test_device_calls_refuse_a_host_only_partition():
                           ctypes.c_void_p(512), 4, None) == binding.ERR_UNSUPPORTED
 
 
+def test_reserve_refuses_a_host_only_partition():
+    part = binding.mgg_build_partition(np.array([0, 1, 2]), np.array([1, 0], dtype=np.int32), host_only=True)
+    lib = binding.lib()
+    assert lib.mgg_partition_reserve(part.handle, 64) == binding.ERR_INVALID_ARG and b"host-only" in lib.mgg_last_error()
+    assert lib.mgg_partition_reserve(None, 64) == binding.ERR_INVALID_ARG
+    assert binding.mgg_aggregate_scratch_bytes(part, 0) == 0
+    assert part.info.reserved_dim == 0
+
+
+def test_binding_checks_what_the_c_abi_cannot_see():
+    """Both embedding tables travel as bare pointers with one leading dimension: a halo table of
+    another dtype, device or row stride, or a buffer with too few rows, is refused before the call."""
+    import torch
+    rng = np.random.default_rng(8)
+    row_ptr, col = inputs.rmat_graph(9, 4000, 0.57, 0.19, 0.19, 0.05, rng)
+    part = binding.mgg_build_partition(row_ptr, col, 2, 0, None, host_only=True)
+    n, h = int(part.info.n_own), int(part.info.num_halo)
+    assert h > 0
+    xl, xh = torch.zeros(n, 16), torch.zeros(h, 16)
+    out = torch.zeros(n, 16)
+    cases = {
+        "stride": (xl, torch.zeros(h, 24)[:, :16], out),             # a padded halo table next to a contiguous local one
+        "dtype": (xl, xh.to(torch.bfloat16), out),
+        "short halo": (xl, xh[: h - 1], out),
+        "short local": (xl[: n - 1], xh, out),
+        "short out": (xl, xh, out[: n - 1]),
+        "narrow out": (xl, xh, torch.zeros(n, 8)),
+        "no halo": (xl, None, out),
+    }
+    for name, (a, b, o) in cases.items():
+        with pytest.raises(ValueError):
+            binding.mgg_aggregate(part, "gcn", a, b, out=o)
+    with pytest.raises(ValueError):
+        binding.mgg_layer_forward(part, "gcn", xl, torch.zeros(h, 24)[:, :16], [torch.zeros(16, 4)], ["none"],
+                                  workspace=torch.zeros(8, dtype=torch.uint8))
+    with pytest.raises(ValueError):
+        binding.mgg_layer_forward(part, "gcn", xl, xh, [torch.zeros(16, 4)], ["none"], workspace=torch.zeros(8, dtype=torch.uint8),
+                                  out=torch.zeros(n - 1, 4))
+    # consistent tables pass the checks and reach the library, which refuses the host-only partition
+    with pytest.raises((MggError, TypeError)):
+        binding.mgg_aggregate(part, "gcn", xl, xh, out=out)
+
+
 def test_options_round_trip():
+    assert binding.mgg_get_option("items_per_wave") == 0
+    for v in (1, 8, 64, 0):
+        binding.mgg_set_option("items_per_wave", v)
+        assert binding.mgg_get_option("items_per_wave") == v
+    for bad in (-1, 65):
+        assert _status(binding.mgg_set_option, "items_per_wave", bad) == binding.ERR_INVALID_ARG
     for key in ("split_phases", "lds_halo", "update_stream"):
         old = binding.mgg_get_option(key)
         binding.mgg_set_option(key, 1 - old)
@@ -300,10 +349,16 @@ def test_layer_workspace_bytes_follow_the_order():
         return int(lib.mgg_layer_workspace_bytes(part.handle, ctypes.byref(d)))
 
     r256 = lambda v: -(-v // 256) * 256
-    assert need((100, 40), binding.ORDER_AGG_FIRST) == r256(n * 104 * 4) + 256
-    assert need((100, 40), binding.ORDER_UPDATE_FIRST) == r256(n * 40 * 4) + r256(h * 40 * 4) + 256
-    assert need((100, 40, 7), binding.ORDER_AGG_FIRST) == r256(n * 104 * 4) + r256(n * 40 * 4) + 256
-    assert need((100, 40, 7), binding.ORDER_UPDATE_FIRST) == 2 * r256(n * 40 * 4) + r256(h * 40 * 4) + 256
+    # the partial sums of rows cut into several work items pass through the workspace as well
+    si = int(part.info.n_split_items)
+    assert si > 0
+    scr = lambda width: r256(si * width * 4)
+    assert binding.mgg_aggregate_scratch_bytes(part, 100) == si * 104 * 4
+    assert binding.mgg_aggregate_scratch_bytes(part, 40) == si * 40 * 4
+    assert need((100, 40), binding.ORDER_AGG_FIRST) == r256(n * 104 * 4) + scr(104) + 256
+    assert need((100, 40), binding.ORDER_UPDATE_FIRST) == r256(n * 40 * 4) + r256(h * 40 * 4) + scr(40) + 256
+    assert need((100, 40, 7), binding.ORDER_AGG_FIRST) == r256(n * 104 * 4) + r256(n * 40 * 4) + scr(104) + 256
+    assert need((100, 40, 7), binding.ORDER_UPDATE_FIRST) == 2 * r256(n * 40 * 4) + r256(h * 40 * 4) + scr(40) + 256
     # AUTO reorders when the transformed rows are at most 3/4 of the input bytes: 40 * 4 <= 0.75 * 100 * 4
     assert need((100, 40), binding.ORDER_AUTO) == max(need((100, 40), binding.ORDER_AGG_FIRST), need((100, 40), binding.ORDER_UPDATE_FIRST))
     assert need((100, 90), binding.ORDER_AUTO) == need((100, 90), binding.ORDER_AGG_FIRST)
