@@ -3,12 +3,19 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--verify]
 
-A step is one forward pass of every layer of the chosen workload (default: config 2, the
-R-MAT 2^20 share with halo table) with all inputs already resident in HBM.  The timed region
-holds exactly K steps between two device synchronisations.  One JSON line is printed:
-whole-step throughput in GEdges/s, the roofline figures of the dominant kernel (the
-aggregation kernel, bound by HBM bandwidth) from HIP events recorded on the launch stream
-inside the timed region, and the CPU oracle timed on the host cores as a baseline.
+A step is one forward pass of every layer of a workload with all inputs already resident in HBM.
+The timed region holds exactly K steps between two device synchronisations.  With no --config the
+workload is config 4 (the dense power-law graph at dim 602: the largest work of the five on one GPU),
+and configs 5, 2 and 3 are timed after it and reported under "other_configs" of the same line.
+
+One JSON line is printed: whole-step throughput in GEdges/s, the roofline figures of the dominant
+kernel (the aggregation kernel) from HIP events recorded on the launch stream inside the timed
+region, and the CPU oracle timed on the host cores as a baseline.  The roofline object carries three
+byte counts side by side: bytes measured with rocprofv3 counters where the L2 hands requests to the
+memory fabric (`achieved`, `frac`: the fraction of the 8 TB/s HBM peak; read from
+profiles/measured_traffic.json, which records the commit it was measured at), the gather-model
+bytes (every neighbour row counted once per edge; above the HBM peak where caches serve repeats, and
+then labelled as a cache-bandwidth figure), and the compulsory bytes of a perfect cache.
 
 One GPU only: collectives and sharding are not part of this build.
 """
@@ -28,15 +35,23 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
-# HBM bytes per aggregation launch from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), scaled by
-# the factor the same counters read for a plain copy kernel; see profiles/ for the summaries.
-# workload name -> bytes per launch of the dominant aggregation kernel (None = not measured)
-MEASURED_TRAFFIC_BYTES = {
-    "cfg2_rmat20_gcn64_p4": 1896712204,          # profiles/aggregate_cfg2_rmat20_gcn64.md
-    "cfg3_rmat22_gin128_bf16_p8": 4361605664,    # profiles/aggregate_cfg3_rmat22_gin128_bf16.md
-    "cfg4_powerlaw233k_gcn602": 105485911303,    # profiles/aggregate_cfg4_powerlaw233k_gcn602.md
-    "cfg5_rmat2.4M_gcn2layer_p8": 34754240991,   # profiles/aggregate_cfg5_rmat2.4M_gcn_dim100_dim256.md (layer 1, dim 256)
-}
+HEADLINE_CONFIG = 4            # timed when no --config is given; the others follow under "other_configs"
+OTHER_CONFIGS = (5, 2, 3)
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "measured_traffic.json")
+
+
+def measured_traffic(workload: str, layer: int):
+    """Bytes per aggregation launch that crossed from L2 to the memory fabric, from rocprofv3 --pmc runs
+    (read and write requests destined for DRAM, 32-byte units, scaled by what the same counters read for
+    a 1 GiB copy), as recorded in profiles/measured_traffic.json together with the commit the kernels
+    were at.  None when that workload and layer were not measured."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f)
+        e = rec["workloads"][workload][f"layer{layer}"]
+        return {"bytes": int(e["bytes"]), "commit": rec.get("commit"), "profile": e.get("profile")}
+    except (OSError, KeyError, ValueError, TypeError):
+        return None
 
 
 def log(*a):
@@ -69,6 +84,12 @@ def gather_model_bytes(nnz, n_own, dim, elem_bytes, gcn, out_bytes=4):
     per_edge = dim * elem_bytes + 4 + (4 if gcn else 0)
     per_row = dim * elem_bytes + dim * out_bytes + 12
     return nnz * per_edge + n_own * per_row
+
+
+def compulsory_bytes(nnz, n_own, num_halo, dim, elem_bytes, gcn, out_bytes=4):
+    """Bytes a perfect cache would still have to move: every table row once (the owned rows are read
+    at least for their own term), the ids (and GCN factors) once, the output rows once."""
+    return (n_own + num_halo) * dim * elem_bytes + nnz * (4 + (4 if gcn else 0)) + n_own * (dim * out_bytes + 12)
 
 
 def cpu_baseline_leg(w, layer, x_local_np, x_halo_np, halo_gid, n_own, cpu_budget_s):
@@ -111,7 +132,8 @@ ABLATIONS = [
     ("no XCD-aware schedule", {"xcd_min_deg": -1}, {}),
     ("source classes by hash (8 classes, one per XCD)", {"hot_phases": -1}, {}),
     ("no short-row bin", {"short_max": -1}, {}),
-    ("halo rows staged through LDS", {}, {"lds_halo": 1}),
+    ("halo rows staged through LDS, two stages per wavefront (section 5.2)", {}, {"lds_halo": 1}),
+    ("one work item per wavefront (no pipelining across items)", {}, {"items_per_wave": 1}),
     ("no column slabs", {}, {"col_slab_bytes": 1}),
     ("source classes by popularity, 4 hot phases per XCD", {"hot_phases": 4}, {}),
 ]
@@ -494,6 +516,7 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
         out = torch.empty((int(info.n_own), layer.dims[-1]), dtype=torch.float32, device=dev)
         layers.append(dict(layer=layer, xl=xl, xh=xh, ws=ws, agg=agg, hid=hid, out=out, esz=lesz,
                            bytes=gather_model_bytes(nnz, int(info.n_own), d_in, lesz, layer.mode == "gcn", 2 if bf16 else 4),
+                           bytes_c=compulsory_bytes(nnz, int(info.n_own), int(info.num_halo), d_in, lesz, layer.mode == "gcn", 2 if bf16 else 4),
                            flops=sum(2.0 * info.n_own * layer.dims[i] * layer.dims[i + 1] for i in range(len(ws)))))
 
     def step(events=None):
@@ -557,21 +580,48 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
         cold_ms = [float(np.median(v)) for v in cold]
         del scratch
     dom = int(np.argmax([L["bytes"] for L in layers]))
-    achieved = layers[dom]["bytes"] / (agg_ms[dom] * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
+
+    def rates(nbytes, ms):
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        return {"bytes": int(nbytes), "gbs": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
 
     per_layer = []
     for li, L in enumerate(layers):
-        per_layer.append({
+        med = float(np.median(agg_all[li]))
+        mt = measured_traffic(w.name, li)
+        rec = {
             "layer": li, "agg_dim": L["layer"].dims[0], "agg_ms": round(agg_ms[li], 4),
             "agg_gedges_per_s": round(nnz / (agg_ms[li] * 1e-3) / 1e9, 3),
-            "agg_model_gbs": round(L["bytes"] / (agg_ms[li] * 1e-3) / 1e9, 1),
-            "agg_frac_of_hbm_peak": round(L["bytes"] / (agg_ms[li] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-            "agg_ms_median": round(float(np.median(agg_all[li])), 4), "agg_ms_min": round(float(np.min(agg_all[li])), 4),
+            "agg_ms_median": round(med, 4), "agg_ms_min": round(float(np.min(agg_all[li])), 4),
             "agg_ms_cold_cache": None if cold_ms[li] is None else round(cold_ms[li], 4),
+            "agg_model": rates(L["bytes"], agg_ms[li]),              # every neighbour row once per edge: what reaches the CUs
+            "agg_compulsory": rates(L["bytes_c"], agg_ms[li]),       # a perfect cache
+            "agg_measured": None if mt is None else rates(mt["bytes"], agg_ms[li]),   # left L2 for the memory fabric (counters)
             "update_ms": round(upd_ms[li], 4),
             "update_tflops": round(L["flops"] / (upd_ms[li] * 1e-3) / 1e12, 2),
-        })
+        }
+        per_layer.append(rec)
+
+    mt = measured_traffic(w.name, dom)
+    model, comp = per_layer[dom]["agg_model"], per_layer[dom]["agg_compulsory"]
+    if mt is not None:
+        basis, nbytes = "measured", mt["bytes"]
+    else:               # no counter run of this workload on record: the perfect-cache bytes are a lower bound on the traffic
+        basis, nbytes = "compulsory", layers[dom]["bytes_c"]
+    achieved = nbytes / (agg_ms[dom] * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": f"aggregate (layer {dom}, dim {layers[dom]['layer'].dims[0]})",
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "basis": basis,                       # which byte count `achieved` and `frac` use
+        "traffic": None if mt is None else mt["bytes"],
+        "traffic_commit": None if mt is None else mt["commit"],
+        "traffic_profile": None if mt is None else mt["profile"],
+        "kernel_ms": round(agg_ms[dom], 4), "kernel_ms_median": per_layer[dom]["agg_ms_median"],
+        # the same launch against the two model byte counts; the gather-model figure exceeds the HBM peak where
+        # L2 serves repeated rows and is then a statement about cache bandwidth, not about HBM
+        "gather_model": dict(model, bound="l2" if model["frac_of_hbm_peak"] > 1.0 else "hbm"),
+        "compulsory": comp,
+    }
 
     if verify:
         import oracle
@@ -606,11 +656,7 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
                    "nnz_remote": int(info.nnz_remote), "num_halo": int(info.num_halo),
                    "layers": [L["layer"].dims for L in layers], "ps": int(info.ps), "dist": int(info.dist),
                    "short_max": int(info.short_max)},
-        "roofline": {"bound": "hbm", "kernel": f"aggregate (layer {dom}, dim {layers[dom]['layer'].dims[0]})",
-                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": traffic, "algorithmic_bytes": int(layers[dom]["bytes"]),
-                     "kernel_ms": round(agg_ms[dom], 4)},
+        "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "per_layer": per_layer,
     }
@@ -621,9 +667,12 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--config", type=int, default=None, choices=[1, 2, 3, 4, 5],
+                    help="time this config only (default: config 4, then 5, 2 and 3 under other_configs)")
+    ap.add_argument("--time-budget", type=float, default=420.0,
+                    help="seconds after which no further config of other_configs is started")
     ap.add_argument("--verify", action="store_true", help="compare sampled rows with the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the cpu_baseline leg (0 = skip it)")
     ap.add_argument("--ablations", action="store_true",
@@ -662,19 +711,31 @@ def main():
         print(json.dumps({"update_shapes": run_update_shapes(vendor=not args.no_vendor)}), flush=True)
         return
     if args.compare_orders:
-        print(json.dumps(run_orders(args.config)), flush=True)
+        print(json.dumps(run_orders(args.config or HEADLINE_CONFIG)), flush=True)
         return
     if args.calibrate_gather:
         print(json.dumps({"calibrate_gather": calibrate_gather()}), flush=True)
         return
     if args.tune or args.tune_exhaustive:
-        print(json.dumps(run_tuner(args.config, args.tune_exhaustive)), flush=True)
+        print(json.dumps(run_tuner(args.config or 2, args.tune_exhaustive)), flush=True)
         return
     if args.ablations:
-        print(json.dumps({"workload_config": args.config, "ablations": run_ablations(args.config)}), flush=True)
+        cfg = args.config or HEADLINE_CONFIG
+        print(json.dumps({"workload_config": cfg, "ablations": run_ablations(cfg)}), flush=True)
         return
-    res = run(args.config, args.steps, args.warmup, args.verify, args.cpu_seconds, args.calibrate_copy,
+    t_begin = time.time()
+    res = run(args.config or HEADLINE_CONFIG, args.steps, args.warmup, args.verify, args.cpu_seconds, args.calibrate_copy,
               args.cold_iters, args.part_id, args.split)
+    if args.config is None:
+        # the other configs, same protocol, without the CPU leg; each adds its per-layer and roofline figures
+        others = []
+        for cfg in OTHER_CONFIGS:
+            if time.time() - t_begin > args.time_budget:
+                log(f"[bench] time budget reached: config {cfg} not run")
+                continue
+            r = run(cfg, args.steps, args.warmup, args.verify, 0.0, False, args.cold_iters, None, "nodes")
+            others.append({k: r[k] for k in ("value", "unit", "ms_per_step", "steps", "dtype", "config", "roofline", "per_layer")})
+        res["other_configs"] = others
     print(json.dumps(res), flush=True)
 
 
