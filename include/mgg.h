@@ -190,6 +190,20 @@ mgg_status_t mgg_aggregate(const mgg_partition_t *p, mgg_agg_t mode, float eps, 
                            const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x,
                            float *out, int64_t ld_out, void *stream);
 
+/* mgg_aggregate for callers that cannot allocate and hold no reserved partition: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and result as
+ * mgg_aggregate; the partial sums of cut rows go to a fixed 64 MiB array inside the library's device
+ * code (one copy per GPU, held until the process ends) instead of the partition's buffer, so the call
+ * allocates nothing whatever was or was not reserved.  A partition whose partial sums at this width
+ * (mgg_aggregate_scratch_bytes) exceed 64 MiB is refused with MGG_ERR_UNSUPPORTED.  The first call on
+ * a device looks up the array's address (not capturable); every call on a GPU shares that GPU's array,
+ * so calls that may overlap on one GPU -- two streams, two threads, two partitions -- race: order them
+ * on one stream.  The array keeps the last call's contents; nothing needs clearing (every slot read
+ * is written first by the same launch). */
+mgg_status_t mgg_aggregate_static(const mgg_partition_t *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
+                                  const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x,
+                                  float *out, int64_t ld_out, void *stream);
+
 /* mgg_aggregate with a choice of output type: out_dtype MGG_F32 is mgg_aggregate; MGG_BF16 rounds
  * the fp32 sums to bf16 (nearest even) as they are written, out then being [n_own x dim] bf16.  A
  * bf16 MFMA rounds its input the same way, so feeding it the bf16 rows gives the bits it would

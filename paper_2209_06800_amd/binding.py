@@ -27,7 +27,7 @@ _STATUS_NAME = ["OK", "INVALID_ARG", "BAD_GRAPH", "UNSUPPORTED", "ALLOC", "HIP"]
 
 EXPORTED_SYMBOLS = [
     "mgg_build_partition", "mgg_partition_info", "mgg_partition_export", "mgg_partition_destroy",
-    "mgg_partition_reserve", "mgg_aggregate_scratch_bytes", "mgg_aggregate", "mgg_aggregate_to", "mgg_build_bags", "mgg_bag_sum", "mgg_update", "mgg_update_mlp", "mgg_layer_workspace_bytes", "mgg_layer_forward",
+    "mgg_partition_reserve", "mgg_aggregate_scratch_bytes", "mgg_aggregate", "mgg_aggregate_static", "mgg_aggregate_to", "mgg_build_bags", "mgg_bag_sum", "mgg_update", "mgg_update_mlp", "mgg_layer_workspace_bytes", "mgg_layer_forward",
     "mgg_split_edge_balanced", "mgg_set_option", "mgg_get_option", "mgg_time_aggregate",
     "mgg_model_evaluate", "mgg_tuner_create", "mgg_tuner_next", "mgg_tuner_report", "mgg_tuner_result",
     "mgg_tuner_table", "mgg_tuner_destroy", "mgg_tune_aggregate",
@@ -113,6 +113,7 @@ def lib():
         L.mgg_partition_export.argtypes = [C.c_void_p, C.POINTER(PartitionArrays)]
         L.mgg_aggregate.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_int32,
                                     C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
+        L.mgg_aggregate_static.argtypes = L.mgg_aggregate.argtypes
         L.mgg_partition_reserve.argtypes = [C.c_void_p, C.c_int32]
         L.mgg_aggregate_scratch_bytes.restype = C.c_size_t
         L.mgg_aggregate_scratch_bytes.argtypes = [C.c_void_p, C.c_int32]
@@ -369,6 +370,20 @@ def mgg_aggregate(part: Partition, mode: str, x_local, x_halo=None, *, eps: floa
         _check(lib().mgg_aggregate_to(part.handle, _MODE[mode], eps, _torch_dtype_code(x_local), _dev_ptr(x_local),
                                       _dev_ptr(x_halo), dim, _ld(x_local), _torch_dtype_code(out), _dev_ptr(out), _ld(out),
                                       _stream(stream)))
+    return out
+
+
+def mgg_aggregate_static(part: Partition, mode: str, x_local, x_halo=None, *, eps: float = 0.0, out=None,
+                         dim: Optional[int] = None, stream=None):
+    """mgg_aggregate through the library's fixed scratch array: nothing is allocated or reserved
+    (pass `out`, or the output tensor is the one allocation made here, by torch)."""
+    import torch
+    dim = int(x_local.shape[1]) if dim is None else dim
+    if out is None:
+        out = torch.empty((int(part.info.n_own), dim), dtype=torch.float32, device=x_local.device)
+    _check_tables(part, x_local, x_halo, out, dim)
+    _check(lib().mgg_aggregate_static(part.handle, _MODE[mode], eps, _torch_dtype_code(x_local), _dev_ptr(x_local),
+                                      _dev_ptr(x_halo), dim, _ld(x_local), _dev_ptr(out), _ld(out), _stream(stream)))
     return out
 
 

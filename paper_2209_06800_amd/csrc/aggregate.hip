@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "aggregate_kernels.h"
 
@@ -91,6 +92,31 @@ __global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_row
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 }  // namespace
+
+// A fixed scratch array for callers that must not allocate (mgg_aggregate_static).  Each GPU the
+// library runs on holds its own copy; its device address is looked up once per device.
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(64) << 20;
+static __device__ __align__(256) float g_static_scratch[kStaticScratchBytes / sizeof(float)];
+constexpr int kMaxDevices = 64;
+static float *g_static_scratch_ptr[kMaxDevices];      // per device; written once, under the mutex
+static std::mutex g_static_scratch_mutex;
+
+float *static_scratch(size_t *bytes)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { hip_fail(e, "hipGetDevice"); return nullptr; }
+    if (dev < 0 || dev >= kMaxDevices) { fail(MGG_ERR_UNSUPPORTED, "device %d beyond the %d the static scratch is kept for", dev, kMaxDevices); return nullptr; }
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (!g_static_scratch_ptr[dev]) {
+        float *ptr = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(g_static_scratch));
+        if (e != hipSuccess || !ptr) { hip_fail(e, "hipGetSymbolAddress(static scratch)"); return nullptr; }
+        g_static_scratch_ptr[dev] = ptr;
+    }
+    if (bytes) *bytes = kStaticScratchBytes;
+    return g_static_scratch_ptr[dev];
+}
 
 mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
                               const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x, void *out,

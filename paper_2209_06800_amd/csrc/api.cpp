@@ -127,6 +127,22 @@ mgg_status_t mgg_aggregate_to(const mgg_partition_t *p, mgg_agg_t mode, float ep
                             MGG_ACT_NONE, 0, out_dtype);
 }
 
+mgg_status_t mgg_aggregate_static(const mgg_partition_t *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype, const void *x_local,
+                                  const void *x_halo, int32_t dim, int64_t ld_x, float *out, int64_t ld_out, void *stream)
+{
+    mgg_status_t s = check_aggregate(p, mode, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out);
+    if (s != MGG_OK) return s;
+    if (p->n_own == 0) return MGG_OK;
+    size_t cap = 0;
+    float *scratch = static_scratch(&cap);
+    if (!scratch) return MGG_ERR_HIP;
+    const size_t need = scratch_bytes_for(p, dim);
+    if (need > cap)
+        return fail(MGG_ERR_UNSUPPORTED, "partial sums of this partition at width %d take %zu bytes, the fixed scratch array holds %zu", dim, need, cap);
+    return launch_aggregate(p, mode, eps, x_dtype, x_local, x_halo, dim, ld_x, out, ld_out, static_cast<hipStream_t>(stream), nullptr, MGG_ACT_NONE, 0,
+                            MGG_F32, scratch, cap);
+}
+
 size_t mgg_aggregate_scratch_bytes(const mgg_partition_t *p, int32_t dim)
 {
     if (!p || dim < 1) return 0;

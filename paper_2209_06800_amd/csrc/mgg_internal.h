@@ -106,13 +106,15 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
                               void *out, int64_t ld_out, hipStream_t stream, const float *bias = nullptr,
                               mgg_act_t act = MGG_ACT_NONE, int32_t out_dim = 0, mgg_dtype_t out_dtype = MGG_F32,
                               float *scratch = nullptr, size_t scratch_bytes = 0);
+// bias / act: optional epilogue of the final value.  out_dim (0 = dim): columns of `out` that exist
+// when the tables carry padding columns beyond them (dim counts the padded width).  out_dtype BF16: the
+// rows are rounded to bf16 (nearest even) on the way out -- what the bf16 MFMA would do on the way in.
 // scratch / scratch_bytes: where the partial sums of rows cut into several items go; NULL = the partition's
 // own buffer (mgg_partition_reserve).  The launch allocates nothing: too small a buffer is an error.
 inline int64_t scratch_ld_for(int32_t dim) { return (static_cast<int64_t>(dim) + 7) / 8 * 8; }   // rows of partial sums start on 32-byte boundaries
 inline size_t scratch_bytes_for(const mgg_partition *p, int32_t dim) { return static_cast<size_t>(p->n_split_items) * static_cast<size_t>(scratch_ld_for(dim)) * sizeof(float); }
-// bias / act: optional epilogue of the final value.  out_dim (0 = dim): columns of `out` that exist
-// when the tables carry padding columns beyond them (dim counts the padded width).  out_dtype BF16: the
-// rows are rounded to bf16 (nearest even) on the way out -- what the bf16 MFMA would do on the way in.
+// the library's fixed scratch array on the current device (aggregate.hip); NULL + error set on failure
+float *static_scratch(size_t *bytes);
 mgg_status_t launch_update(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, int64_t ld_a, int32_t d_in,
                            mgg_dtype_t w_dtype, const void *w, const float *bias, int32_t d_out,
                            mgg_act_t act, mgg_dtype_t out_dtype, void *out, int64_t ld_out,

@@ -268,11 +268,13 @@ def test_device_calls_refuse_a_host_only_partition():
                           ctypes.c_void_p(512), 4, None) == binding.ERR_UNSUPPORTED
 
 
-def test_reserve_refuses_a_host_only_partition():
+def test_reserve_and_static_calls_refuse_a_host_only_partition():
     part = binding.mgg_build_partition(np.array([0, 1, 2]), np.array([1, 0], dtype=np.int32), host_only=True)
     lib = binding.lib()
     assert lib.mgg_partition_reserve(part.handle, 64) == binding.ERR_INVALID_ARG and b"host-only" in lib.mgg_last_error()
     assert lib.mgg_partition_reserve(None, 64) == binding.ERR_INVALID_ARG
+    st = lib.mgg_aggregate_static(part.handle, 0, 0.0, 0, ctypes.c_void_p(256), None, 4, 4, ctypes.c_void_p(512), 4, None)
+    assert st == binding.ERR_INVALID_ARG and b"host-only" in lib.mgg_last_error()
     assert binding.mgg_aggregate_scratch_bytes(part, 0) == 0
     assert part.info.reserved_dim == 0
 
@@ -300,6 +302,8 @@ def test_binding_checks_what_the_c_abi_cannot_see():
     for name, (a, b, o) in cases.items():
         with pytest.raises(ValueError):
             binding.mgg_aggregate(part, "gcn", a, b, out=o)
+        with pytest.raises(ValueError):
+            binding.mgg_aggregate_static(part, "gcn", a, b, out=o)
     with pytest.raises(ValueError):
         binding.mgg_layer_forward(part, "gcn", xl, torch.zeros(h, 24)[:, :16], [torch.zeros(16, 4)], ["none"],
                                   workspace=torch.zeros(8, dtype=torch.uint8))
