@@ -98,7 +98,8 @@ def cpu_baseline_leg(w, layer, x_local_np, x_halo_np, halo_gid, n_own, cpu_budge
     import oracle
     deg_share = (np.diff(w.row_ptr)[w.lb:w.ub]).astype(np.int64)
     work = deg_share * w.dim
-    budget = cpu_budget_s * 0.6e9 * max(1, oracle.num_threads()) / 8.0
+    # about 1.2e9 multiply-adds per second and thread (measured on the box's EPYC cores)
+    budget = cpu_budget_s * 1.2e9 * max(1, oracle.num_threads())
     rows = np.arange(n_own)
     if work.sum() > budget:
         rng = np.random.default_rng(1)
@@ -697,6 +698,8 @@ def main():
     ap.add_argument("--calibrate-gather", action="store_true",
                     help="launch the aggregation kernel on a graph that gathers each of 4 Mi table rows exactly once "
                          "(known L2-miss bytes; reference for rocprofv3 --pmc runs) and exit")
+    ap.add_argument("--option", action="append", default=[], metavar="KEY=VALUE",
+                    help="a run-time switch of the library (mgg_set_option) for the whole run, e.g. col_slab_bytes=128")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a 1 GiB device copy three times (reference for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -704,6 +707,10 @@ def main():
         print("bench.py measures one GPU's share on one MI355X; multi-GPU runs are not part of this build "
               "(no collectives, no second GPU). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    for kv in args.option:
+        from paper_2209_06800_amd import binding
+        key, _, val = kv.partition("=")
+        binding.mgg_set_option(key, int(val))
     if args.embedding_bags:
         print(json.dumps(run_embedding_bags()), flush=True)
         return
