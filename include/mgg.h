@@ -333,6 +333,11 @@ mgg_status_t mgg_split_edge_balanced(int64_t num_nodes, const int64_t *row_ptr, 
  * in a lookup table and the lowest latency wins.  Usage: call mgg_tuner_next (it proposes a
  * configuration, or sets *done), measure it, call mgg_tuner_report with the latency (any unit),
  * repeat.  mgg_tuner_table copies up to `capacity` trials in the order they were made.
+ * mgg_tuner_set_constraint (before the first trial; dim 0 = none) bounds the search space by the
+ * model's constraint on shared memory: a configuration with smem_bytes(ps, wpb, dim) above the
+ * limit is never proposed and counts as slower than anything measured (an upward step onto it does
+ * not pay, a retreat trial on it ends the search).  mgg_tune_aggregate sets it to its `dim` and the
+ * 160 KB of LDS per CU unless the caller has set one.
  *
  * mgg_tune_aggregate drives a tuner on the GPU: for every proposal it builds the partition with
  * base_opts (NULL = defaults) plus the proposed ps / dist / wpb, times `iters` aggregations on
@@ -350,6 +355,7 @@ typedef struct mgg_tuner mgg_tuner_t;
 mgg_status_t mgg_model_evaluate(int64_t n_local_partitions, int64_t n_remote_partitions, mgg_knobs_t knobs,
                                 int32_t dim, int32_t num_units, int64_t smem_limit_bytes, mgg_model_t *out);
 mgg_status_t mgg_tuner_create(int32_t ps_max, int32_t dist_max, int32_t wpb_max, mgg_tuner_t **out);
+mgg_status_t mgg_tuner_set_constraint(mgg_tuner_t *t, int32_t dim, int64_t smem_limit_bytes);
 mgg_status_t mgg_tuner_next(mgg_tuner_t *t, mgg_knobs_t *next, int32_t *done);
 mgg_status_t mgg_tuner_report(mgg_tuner_t *t, double latency);
 mgg_status_t mgg_tuner_result(const mgg_tuner_t *t, mgg_knobs_t *best, double *best_latency, int32_t *n_trials);

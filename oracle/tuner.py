@@ -19,7 +19,10 @@ block), written out plainly:
 Readings where the text is silent: "increase" doubles the knob (the search spaces are
 1..32, 1..16, 1..16 and the paper reports about ten trials); an increase that would leave the
 range ends its step; "restart the increase of wpb" restarts it from 1; a configuration that
-is already in the table is not measured twice.
+is already in the table is not measured twice.  The model's constraints (section 6, constraint on
+SMEM) bound the search space: a configuration that violates them is never measured and never
+enters the table; where the search would try one, it counts as slower than anything measured
+(an upward step onto it does not pay; a retreat trial on it ends the search).
 """
 from __future__ import annotations
 
@@ -41,13 +44,17 @@ def model(n_local: int, n_remote: int, ps: int, dist: int, wpb: int, dim: int,
             "blocks_per_unit": num_blocks / num_units, "feasible": smem <= smem_limit}
 
 
-def search(latency: Callable[[Knobs], float], ps_max: int = 32, dist_max: int = 16, wpb_max: int = 16):
+def search(latency: Callable[[Knobs], float], ps_max: int = 32, dist_max: int = 16, wpb_max: int = 16,
+           feasible: Callable[[Knobs], bool] = None):
     """Runs the search against a latency function.  Returns (best knobs, table) where table is
-    the list of (knobs, latency) in the order the trials were made."""
+    the list of (knobs, latency) in the order the trials were made; best is None when not even the
+    starting point is feasible."""
     table: List[Tuple[Knobs, float]] = []
     seen: Dict[Knobs, float] = {}
 
     def measure(k: Knobs) -> float:
+        if feasible is not None and not feasible(k):
+            return float("inf")
         if k not in seen:
             seen[k] = latency(k)
             table.append((k, seen[k]))
@@ -66,7 +73,7 @@ def search(latency: Callable[[Knobs], float], ps_max: int = 32, dist_max: int = 
             cur, best_lat = trial, lat
     def third_lowest() -> float:
         lats = sorted(v for _, v in table)
-        return lats[min(2, len(lats) - 1)]
+        return lats[min(2, len(lats) - 1)] if lats else float("inf")
 
     ps, dist = cur[0], cur[1]
     stop = False
@@ -84,5 +91,5 @@ def search(latency: Callable[[Knobs], float], ps_max: int = 32, dist_max: int = 
             if lat2 >= lat:
                 break
             wpb, lat = wpb * 2, lat2
-    best = min(table, key=lambda kv: kv[1])[0]  # step 6
+    best = min(table, key=lambda kv: kv[1])[0] if table else None  # step 6
     return best, table

@@ -29,7 +29,7 @@ EXPORTED_SYMBOLS = [
     "mgg_build_partition", "mgg_partition_info", "mgg_partition_export", "mgg_partition_destroy",
     "mgg_partition_reserve", "mgg_aggregate_scratch_bytes", "mgg_aggregate", "mgg_aggregate_static", "mgg_aggregate_to", "mgg_build_bags", "mgg_bag_sum", "mgg_update", "mgg_update_mlp", "mgg_layer_workspace_bytes", "mgg_layer_forward",
     "mgg_split_edge_balanced", "mgg_set_option", "mgg_get_option", "mgg_time_aggregate",
-    "mgg_model_evaluate", "mgg_tuner_create", "mgg_tuner_next", "mgg_tuner_report", "mgg_tuner_result",
+    "mgg_model_evaluate", "mgg_tuner_create", "mgg_tuner_set_constraint", "mgg_tuner_next", "mgg_tuner_report", "mgg_tuner_result",
     "mgg_tuner_table", "mgg_tuner_destroy", "mgg_tune_aggregate",
     "mgg_last_error", "mgg_version",
 ]
@@ -141,6 +141,7 @@ def lib():
         L.mgg_model_evaluate.argtypes = [C.c_int64, C.c_int64, Knobs, C.c_int32, C.c_int32, C.c_int64,
                                          C.POINTER(Model)]
         L.mgg_tuner_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+        L.mgg_tuner_set_constraint.argtypes = [C.c_void_p, C.c_int32, C.c_int64]
         L.mgg_tuner_next.argtypes = [C.c_void_p, C.POINTER(Knobs), C.POINTER(C.c_int32)]
         L.mgg_tuner_report.argtypes = [C.c_void_p, C.c_double]
         L.mgg_tuner_result.argtypes = [C.c_void_p, C.POINTER(Knobs), C.POINTER(C.c_double), C.POINTER(C.c_int32)]
@@ -506,6 +507,10 @@ class Tuner:
         if self._h is None:
             raise ValueError("tuner already destroyed")
         return self._h
+
+    def set_constraint(self, dim: int, smem_limit_bytes: int = 160 * 1024):
+        """Bound the search space by the model's shared-memory constraint (before the first trial)."""
+        _check(lib().mgg_tuner_set_constraint(self.handle, int(dim), int(smem_limit_bytes)))
 
     def next(self):
         """The next configuration (ps, dist, wpb) to measure, or None when the search is over."""

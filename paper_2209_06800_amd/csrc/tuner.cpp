@@ -6,6 +6,7 @@
 // there is no hidden state beyond the table: the next proposal is found by replaying the
 // search against the table until it asks for a configuration that has not been measured.
 #include <algorithm>
+#include <limits>
 #include <new>
 #include <vector>
 
@@ -13,6 +14,8 @@
 
 struct mgg_tuner {
     int32_t limit[3] = {32, 16, 16};
+    int32_t dim = 0;                 // > 0: the model's shared-memory constraint bounds the search space
+    int64_t smem_limit = 0;
     std::vector<mgg_knobs_t> knobs;
     std::vector<double> latency;
     mgg_knobs_t pending{0, 0, 0};
@@ -35,18 +38,29 @@ bool lookup(const mgg_tuner *t, const mgg_knobs_t &k, double *lat, size_t *made)
 // third-lowest latency among the first n_trials trials
 double third_lowest(const mgg_tuner *t, size_t n_trials)
 {
+    if (n_trials == 0) return std::numeric_limits<double>::infinity();
     std::vector<double> v(t->latency.begin(), t->latency.begin() + n_trials);
     std::sort(v.begin(), v.end());
     return v[std::min<size_t>(2, v.size() - 1)];
+}
+
+// the model's constraint on shared memory (section 6): SMEM = ps wpb IntS + 2 wpb D FloatS <= limit
+bool feasible(const mgg_tuner *t, const mgg_knobs_t &k)
+{
+    if (t->dim <= 0) return true;
+    const int64_t smem = static_cast<int64_t>(k.ps) * k.wpb * 4 + 2 * static_cast<int64_t>(k.wpb) * t->dim * 4;
+    return smem <= t->smem_limit;
 }
 
 // Replays the search.  Returns true when it has run to its end; otherwise *need is the
 // configuration whose latency is missing.
 bool replay(const mgg_tuner *t, mgg_knobs_t *need)
 {
+    // a configuration outside the model's constraints is never measured: slower than anything that was
 #define MGG_MEASURE(k, var)                       \
     do {                                          \
-        if (!lookup(t, (k), &(var), &made)) { *need = (k); return false; } \
+        if (!feasible(t, (k))) (var) = std::numeric_limits<double>::infinity(); \
+        else if (!lookup(t, (k), &(var), &made)) { *need = (k); return false; } \
     } while (0)
 
     int32_t cur[3] = {1, 1, 1};
@@ -121,6 +135,16 @@ mgg_status_t mgg_tuner_create(int32_t ps_max, int32_t dist_max, int32_t wpb_max,
     return MGG_OK;
 }
 
+mgg_status_t mgg_tuner_set_constraint(mgg_tuner_t *t, int32_t dim, int64_t smem_limit_bytes)
+{
+    if (!t) return fail(MGG_ERR_INVALID_ARG, "tuner is NULL");
+    if (dim < 0 || smem_limit_bytes < 0) return fail(MGG_ERR_INVALID_ARG, "dim %d, limit %lld", dim, (long long)smem_limit_bytes);
+    if (!t->knobs.empty() || t->has_pending) return fail(MGG_ERR_INVALID_ARG, "the constraint has to be set before the first trial");
+    t->dim = dim;
+    t->smem_limit = smem_limit_bytes;
+    return MGG_OK;
+}
+
 mgg_status_t mgg_tuner_next(mgg_tuner_t *t, mgg_knobs_t *next, int32_t *done)
 {
     if (!t || !next || !done) return fail(MGG_ERR_INVALID_ARG, "NULL argument");
@@ -176,6 +200,8 @@ mgg_status_t mgg_tune_aggregate(int64_t num_nodes, const int64_t *row_ptr, const
                                 mgg_tuner_t *tuner, mgg_knobs_t *best, double *best_ms)
 {
     if (!tuner) return fail(MGG_ERR_INVALID_ARG, "tuner is NULL");
+    // the model's resource constraint, evaluated for this width and the LDS of one compute unit
+    if (tuner->dim <= 0 && tuner->knobs.empty() && !tuner->has_pending && dim > 0) { tuner->dim = dim; tuner->smem_limit = 160 * 1024; }
     mgg_build_opts_t o{};
     if (base_opts) o = *base_opts;
     o.host_only = 0;

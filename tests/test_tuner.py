@@ -90,17 +90,47 @@ def test_search_respects_the_ranges():
     assert best == (1, 1, 1)
 
 
+def test_search_inside_the_models_constraint_worked_by_hand():
+    # D = 64 and a shared-memory limit of 1200 bytes: SMEM = 4 ps wpb + 512 wpb allows wpb 1 for every ps,
+    # wpb 2 up to ps 22, and never wpb 4.  Latency 1 + |log2 ps - 4| + 0.5 |log2 dist - 1| + 0.25 |log2 wpb - 3|
+    # (lowest at ps 16, dist 2, wpb 8, which the constraint excludes).  By hand:
+    #   ps:    (1,1,1) 6.25, (2,1,1) 5.25, (4,1,1) 4.25, (8,1,1) 3.25, (16,1,1) 2.25, (32,1,1) 3.25 -> ps 16
+    #   dist:  (16,2,1) 1.75, (16,4,1) 2.25                                                        -> dist 2
+    #   wpb:   (16,2,2) 1.5 [SMEM 1152], (16,2,4) infeasible [SMEM 2304]: not measured             -> wpb 2
+    #   retreat: (8,2,1) 2.75 > third lowest (2.25): the search ends
+    def latency(k):
+        return 1 + abs(np.log2(k[0]) - 4) + 0.5 * abs(np.log2(k[1]) - 1) + 0.25 * abs(np.log2(k[2]) - 3)
+
+    feasible = lambda k: otuner.model(1, 1, k[0], k[1], k[2], 64, 256, 1200)["feasible"]
+    best, table = otuner.search(latency, feasible=feasible)
+    assert [k for k, _ in table] == [(1, 1, 1), (2, 1, 1), (4, 1, 1), (8, 1, 1), (16, 1, 1), (32, 1, 1), (16, 2, 1), (16, 4, 1),
+                                     (16, 2, 2), (8, 2, 1)]
+    assert [v for _, v in table] == [6.25, 5.25, 4.25, 3.25, 2.25, 3.25, 1.75, 2.25, 1.5, 2.75]
+    assert best == (16, 2, 2)
+    # without the constraint the wpb sweep goes on to 8
+    assert otuner.search(latency)[0] == (16, 2, 8)
+    # nothing feasible at all: no trial is made
+    assert otuner.search(latency, feasible=lambda k: False) == (None, [])
+
+
 # ------------------------------------------------------------------------------ library vs oracle
-def _drive(latency, limits=(32, 16, 16)):
+def _drive(latency, limits=(32, 16, 16), constraint=None):
     t = binding.Tuner(*limits)
+    if constraint is not None:
+        t.set_constraint(*constraint)
     while True:
         k = t.next()
         if k is None:
             break
         assert t.next() == k                                       # asking twice proposes the same trial
         t.report(latency(k))
-    best, best_lat, n = t.result()
     table = t.table()
+    if not table:                                                  # not even the starting point was feasible
+        with pytest.raises(binding.MggError):
+            t.result()
+        t.destroy()
+        return None, table
+    best, best_lat, n = t.result()
     t.destroy()
     assert n == len(table) and best_lat == min(v for _, v in table)
     return best, table
@@ -131,6 +161,32 @@ def test_library_search_makes_the_oracles_trials(seed):
     best, table = _drive(lambda k: lat[k])
     assert table == want_table
     assert best == want_best
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_library_search_inside_the_models_constraint(seed):
+    """With mgg_tuner_set_constraint the library skips what the model calls infeasible, exactly as the oracle does."""
+    rng = np.random.default_rng(5000 + seed)
+    grid = list(itertools.product(POW2[32], POW2[16], POW2[16]))
+    opt = np.log2([rng.choice(POW2[32]), rng.choice(POW2[16]), rng.choice(POW2[16])])
+    lat = {k: float(1 + np.abs(np.log2(k) - opt).sum() + rng.uniform(0, 0.3)) for k in grid}
+    dim = int(rng.choice([16, 64, 602, 4096]))
+    limit = int(rng.choice([8 * dim - 1, 8 * dim + 4, 20 * dim, 70 * dim, 160 * 1024]))
+    feasible = lambda k: otuner.model(1, 1, k[0], k[1], k[2], dim, 256, limit)["feasible"]
+    want_best, want_table = otuner.search(lambda k: lat[k], feasible=feasible)
+    best, table = _drive(lambda k: lat[k], constraint=(dim, limit))
+    assert table == want_table and best == want_best
+    assert all(feasible(k) for k, _ in table)
+
+
+def test_constraint_has_to_come_before_the_first_trial():
+    t = binding.Tuner()
+    t.set_constraint(64, 1200)
+    t.next()
+    t.report(1.0)
+    with pytest.raises(binding.MggError):
+        t.set_constraint(64, 4000)
+    t.destroy()
 
 
 def test_library_search_with_ties_and_small_ranges():
