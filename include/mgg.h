@@ -80,8 +80,9 @@ typedef struct {
                               laid out for; sets hot_rows = 3 MB / (row bytes in whole 128-byte
                               lines) when hot_rows is 0; 0 = 256 */
     int32_t hot_rows;      /* table rows per XCD and phase; 0 = from hot_row_bytes */
-    int32_t hot_phases;    /* most phases (1..31); negative = 8 classes by a hash of the table row
-                              index, no cold class; 0 = automatic */
+    int32_t hot_phases;    /* most phases (1..31); negative = classes by a hash of the table row index, no
+                              cold class: -1 gives 8 classes, one per XCD; -2, -4, ... -16 give 16, 32, ...
+                              128, XCD x working through classes x, x + 8, ... in turn; 0 = automatic */
     int32_t min_piece;     /* a class with fewer neighbours than this in a row joins the row's
                               cold piece; 0 = default 16 */
     int32_t hot_min_count; /* table rows gathered fewer times than this are cold; 0 = default 8 */

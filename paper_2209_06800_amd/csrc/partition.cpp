@@ -94,7 +94,7 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Class of an embedding-table row (a multiplicative hash, so that classes are balanced even when
 // hubs crowd the low ids).
-static inline int source_class(int32_t row) { return static_cast<int>((static_cast<uint32_t>(row) * 0x9E3779B1u) >> 29); }
+static inline int source_class(int32_t row, int bits = 3) { return static_cast<int>((static_cast<uint32_t>(row) * 0x9E3779B1u) >> (32 - bits)); }
 
 static void export_groups(const std::vector<int32_t> &rp, int32_t ps, int32_t *row, int32_t *start, int32_t *end)
 {
@@ -209,9 +209,13 @@ static void build_schedule(mgg_partition *p, const Knobs &k)
         }
         p->class_mode = hot_phases < 0 ? 1 : 2;
         if (hot_phases < 0) {
+            // -1: 8 hash classes, one per XCD; -2, -4, ...: 16, 32, ... hash classes, XCD x working through
+            // classes x, x + 8, ... one after the other (each holds a smaller share of the table rows)
+            int bits = 3;
             n_phase = 1;
-            for (int64_t i = 0; i < n_loc; ++i) p->src_class[i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
-            for (int64_t i = 0; i < num_halo; ++i) p->src_class[n_loc + i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i)));
+            while (n_phase * 2 <= -hot_phases && n_phase * 2 <= 16) { n_phase *= 2; ++bits; }
+            for (int64_t i = 0; i < n_loc; ++i) p->src_class[i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i), bits));
+            for (int64_t i = 0; i < num_halo; ++i) p->src_class[n_loc + i] = static_cast<uint8_t>(source_class(static_cast<int32_t>(i), bits));
         } else if (n_tab > 0) {
             const int64_t limit = std::min<int64_t>(n_tab, per_phase * hot_phases);
             int64_t r = 0;

@@ -142,7 +142,8 @@ def test_aggregate_bf16_dims(dim):
                                    dict(wpb=1), dict(wpb=2, xcd_min_deg=40), dict(wpb=8), dict(wpb=16, ps=16, dist=2),
                                    dict(hot_phases=4, xcd_min_deg=40), dict(hot_phases=1, hot_rows=64, min_piece=1, xcd_min_deg=1),
                                    dict(hot_phases=31, hot_rows=16, min_piece=4, hot_min_count=2, xcd_min_deg=20, ps=8, dist=1),
-                                   dict(hot_phases=2, hot_row_bytes=1024, min_piece=64, xcd_min_deg=100)])
+                                   dict(hot_phases=2, hot_row_bytes=1024, min_piece=64, xcd_min_deg=100),
+                                   dict(hot_phases=-2, xcd_min_deg=40), dict(hot_phases=-16, xcd_min_deg=20, min_piece=2)])
 def test_every_schedule_gives_the_same_answer(build):
     """Neighbour-partition size, pairs per work item and the short-row bin change only the
     schedule (section 4.1 Step-3, section 5.1), never the value."""
