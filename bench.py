@@ -272,6 +272,19 @@ def calibrate_gather(dims=(64, 100, 256), n_halo: int = 1 << 22, per_row: int = 
     return out_lines
 
 
+def probe_gather():
+    """The rate at which the memory hierarchy delivers gathered rows to the CUs, by where the rows live:
+    random rows of 256 bytes and of 1 KB from tables between 1 MB (inside one XCD's L2) and 2 GB (HBM)."""
+    from paper_2209_06800_amd import binding
+    rows = []
+    for row_bytes in (256, 1024):
+        for mb in (1, 2, 3, 4, 5, 6, 7, 8, 12, 16, 32, 64, 256, 2048):
+            gbs = binding.mgg_probe_gather(mb << 20, row_bytes)
+            rows.append({"row_bytes": row_bytes, "table_mb": mb, "gathered_gbs": round(gbs, 1)})
+            log(f"[probe-gather] rows of {row_bytes} B from a {mb} MB table: {gbs / 1e3:.2f} TB/s")
+    return rows
+
+
 def run_orders(cfg: int, iters: int = 20):
     """Whole-layer time (mgg_layer_forward, HIP events on the launch stream) with the aggregation
     first -- the paper's formulation -- and with the first matrix product first, which gathers
@@ -700,6 +713,8 @@ def main():
                          "(known L2-miss bytes; reference for rocprofv3 --pmc runs) and exit")
     ap.add_argument("--option", action="append", default=[], metavar="KEY=VALUE",
                     help="a run-time switch of the library (mgg_set_option) for the whole run, e.g. col_slab_bytes=128")
+    ap.add_argument("--probe-gather", action="store_true",
+                    help="time a bare gather kernel on tables from 1 MB to 2 GB (the ceilings of the gather path) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a 1 GiB device copy three times (reference for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -719,6 +734,9 @@ def main():
         return
     if args.compare_orders:
         print(json.dumps(run_orders(args.config or HEADLINE_CONFIG)), flush=True)
+        return
+    if args.probe_gather:
+        print(json.dumps({"probe_gather": probe_gather()}), flush=True)
         return
     if args.calibrate_gather:
         print(json.dumps({"calibrate_gather": calibrate_gather()}), flush=True)

@@ -63,7 +63,7 @@ typedef struct {
                             checks of the integer structures); device calls on such a
                             partition fail with MGG_ERR_INVALID_ARG */
     int32_t wpb;         /* wavefronts (= work items) per workgroup of the aggregation kernel,
-                            1..16; 0 = default 4 */
+                            1..16; 0 = default 2 */
     int32_t xcd_min_deg; /* rows with at least this many neighbours have their neighbour lists
                             regrouped by source class (see hot_rows), one piece of work per
                             class; 0 = library default, negative = no classes at all */
@@ -392,6 +392,16 @@ mgg_status_t mgg_get_option(const char *key, int32_t *value);
 mgg_status_t mgg_time_aggregate(const mgg_partition_t *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
                                 const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x,
                                 float *out, int64_t ld_out, void *stream, int32_t iters, float *ms_per_call);
+
+/* Measurement aid for the roofline of the aggregation (section 3.1 of the paper frames the aggregation as
+ * bound by irregular, fine-grained remote and local loads): gathers n_gathers rows of row_bytes (128, 256,
+ * 512 or 1024) by seeded random ids from a zero-filled table of table_bytes that the call allocates on the
+ * current device, with the aggregation kernel's load shape (16 bytes per lane, eight loads in flight) and no
+ * other work, `iters` launches timed with HIP events on the default stream; returns gathered GB/s.  Host call,
+ * synchronous, allocates and frees.  The table size decides where the rows come from: a few MB stay in one
+ * XCD's L2, up to 256 MB in the Infinity Cache, beyond that in HBM.  Errors: INVALID_ARG, ALLOC, HIP. */
+mgg_status_t mgg_probe_gather(int64_t table_bytes, int32_t row_bytes, int64_t n_gathers, int32_t iters, uint64_t seed,
+                              double *gbytes_per_s);
 
 const char *mgg_last_error(void);      /* thread-local, never NULL */
 const char *mgg_version(void);

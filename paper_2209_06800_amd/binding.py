@@ -28,7 +28,7 @@ _STATUS_NAME = ["OK", "INVALID_ARG", "BAD_GRAPH", "UNSUPPORTED", "ALLOC", "HIP"]
 EXPORTED_SYMBOLS = [
     "mgg_build_partition", "mgg_partition_info", "mgg_partition_export", "mgg_partition_destroy",
     "mgg_partition_reserve", "mgg_aggregate_scratch_bytes", "mgg_aggregate", "mgg_aggregate_static", "mgg_aggregate_to", "mgg_build_bags", "mgg_bag_sum", "mgg_update", "mgg_update_mlp", "mgg_layer_workspace_bytes", "mgg_layer_forward",
-    "mgg_split_edge_balanced", "mgg_set_option", "mgg_get_option", "mgg_time_aggregate",
+    "mgg_split_edge_balanced", "mgg_set_option", "mgg_get_option", "mgg_time_aggregate", "mgg_probe_gather",
     "mgg_model_evaluate", "mgg_tuner_create", "mgg_tuner_set_constraint", "mgg_tuner_next", "mgg_tuner_report", "mgg_tuner_result",
     "mgg_tuner_table", "mgg_tuner_destroy", "mgg_tune_aggregate",
     "mgg_last_error", "mgg_version",
@@ -138,6 +138,7 @@ def lib():
         L.mgg_time_aggregate.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p,
                                          C.c_int32, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                                          C.POINTER(C.c_float)]
+        L.mgg_probe_gather.argtypes = [C.c_int64, C.c_int32, C.c_int64, C.c_int32, C.c_uint64, C.POINTER(C.c_double)]
         L.mgg_model_evaluate.argtypes = [C.c_int64, C.c_int64, Knobs, C.c_int32, C.c_int32, C.c_int64,
                                          C.POINTER(Model)]
         L.mgg_tuner_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
@@ -403,6 +404,13 @@ def mgg_time_aggregate(part: Partition, mode: str, x_local, x_halo, out, *, eps:
                                     _dev_ptr(x_halo), dim, _ld(x_local), _dev_ptr(out), _ld(out), _stream(stream),
                                     iters, C.byref(ms)))
     return float(ms.value)
+
+
+def mgg_probe_gather(table_bytes: int, row_bytes: int = 256, n_gathers: int = 1 << 24, iters: int = 5, seed: int = 7) -> float:
+    """Gathered GB/s of random rows from a table of the given size (measurement aid, see mgg.h)."""
+    gbs = C.c_double()
+    _check(lib().mgg_probe_gather(int(table_bytes), int(row_bytes), int(n_gathers), int(iters), int(seed), C.byref(gbs)))
+    return float(gbs.value)
 
 
 def mgg_update(a, w, bias=None, act: str = "none", *, out=None, out_dtype=None, stream=None):

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <mutex>
+#include <vector>
 
 #include "aggregate_kernels.h"
 
@@ -91,6 +92,37 @@ __global__ __launch_bounds__(kBlock) void fixup_kernel(const SplitRow *split_row
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+// Measurement aid: rows of row_bytes gathered by pre-drawn random ids from a table of table_rows rows, 16-byte
+// loads, eight in flight per lane, nothing but an add per element -- the rate at which the memory hierarchy
+// delivers gathered rows to the CUs when the kernel around the gathers costs nothing.
+template <int LPR>
+__global__ __launch_bounds__(256) void probe_gather_kernel(const float4 *__restrict__ table, const int32_t *__restrict__ idx, int per_wave, float *sink)
+{
+    constexpr int NPW = kWave / LPR;
+    const int lane = threadIdx.x & (kWave - 1), sub = lane / LPR, lis = lane % LPR;
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave;
+    const int32_t *my = idx + wave * per_wave;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    int ids = my[lane];
+    for (int g = 0; g < per_wave; g += kWave) {
+        const int nxt = g + kWave < per_wave ? my[g + kWave + lane] : 0;
+#pragma unroll
+        for (int t0 = 0; t0 < kWave / NPW; t0 += 8) {
+            float4 r[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int j = (t0 + u) * NPW + sub;
+                const int id = NPW == 1 ? __builtin_amdgcn_readlane(ids, j) : __shfl(ids, j);
+                r[u] = table[static_cast<int64_t>(id) * LPR + lis];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { acc.x += r[u].x; acc.y += r[u].y; acc.z += r[u].z; acc.w += r[u].w; }
+        }
+        ids = nxt;
+    }
+    if (acc.x + acc.y + acc.z + acc.w == 12345.678f) sink[0] = acc.x;     // keeps the loads alive
+}
+
 }  // namespace
 
 // A fixed scratch array for callers that must not allocate (mgg_aggregate_static).  Each GPU the
@@ -116,6 +148,61 @@ float *static_scratch(size_t *bytes)
     }
     if (bytes) *bytes = kStaticScratchBytes;
     return g_static_scratch_ptr[dev];
+}
+
+mgg_status_t probe_gather(int64_t table_bytes, int32_t row_bytes, int64_t n_gathers, int32_t iters, uint64_t seed, double *gbs)
+{
+    if (row_bytes != 128 && row_bytes != 256 && row_bytes != 512 && row_bytes != 1024)
+        return fail(MGG_ERR_INVALID_ARG, "row_bytes must be 128, 256, 512 or 1024");
+    constexpr int per_wave = 512, wpb = 4;
+    if (table_bytes < row_bytes || table_bytes > (static_cast<int64_t>(8) << 30) || n_gathers < per_wave * wpb || n_gathers > (static_cast<int64_t>(1) << 28) ||
+        iters < 1 || !gbs)
+        return fail(MGG_ERR_INVALID_ARG, "probe sizes out of range");
+    const int64_t rows = table_bytes / row_bytes;
+    const int64_t waves = n_gathers / per_wave / wpb * wpb;
+    n_gathers = waves * per_wave;
+    float4 *table = nullptr;
+    int32_t *idx = nullptr;
+    float *sink = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    std::vector<int32_t> h(static_cast<size_t>(n_gathers));
+    uint64_t x = seed * 0x9E3779B97F4A7C15ull + 1;
+    for (auto &v : h) {                                   // splitmix64
+        x += 0x9E3779B97F4A7C15ull;
+        uint64_t z = x;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull; z = (z ^ (z >> 27)) * 0x94D049BB133111EBull; z ^= z >> 31;
+        v = static_cast<int32_t>(z % static_cast<uint64_t>(rows));
+    }
+    mgg_status_t st = MGG_OK;
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&table), static_cast<size_t>(rows) * row_bytes);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&idx), h.size() * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&sink), sizeof(float));
+    if (e != hipSuccess) st = fail(MGG_ERR_ALLOC, "probe buffers: %s", hipGetErrorString(e));
+    if (st == MGG_OK) {
+        e = hipMemset(table, 0, static_cast<size_t>(rows) * row_bytes);
+        if (e == hipSuccess) e = hipMemcpy(idx, h.data(), h.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipEventCreate(&e0);
+        if (e == hipSuccess) e = hipEventCreate(&e1);
+        const dim3 grid(static_cast<unsigned>(waves / wpb)), block(kWave * wpb);
+        for (int it = -2; it < iters && e == hipSuccess; ++it) {           // two untimed launches first
+            if (it == 0) e = hipEventRecord(e0, nullptr);
+            if (row_bytes == 128) hipLaunchKernelGGL(probe_gather_kernel<8>, grid, block, 0, nullptr, table, idx, per_wave, sink);
+            else if (row_bytes == 256) hipLaunchKernelGGL(probe_gather_kernel<16>, grid, block, 0, nullptr, table, idx, per_wave, sink);
+            else if (row_bytes == 512) hipLaunchKernelGGL(probe_gather_kernel<32>, grid, block, 0, nullptr, table, idx, per_wave, sink);
+            else hipLaunchKernelGGL(probe_gather_kernel<64>, grid, block, 0, nullptr, table, idx, per_wave, sink);
+            if (e == hipSuccess) e = hipGetLastError();
+        }
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventRecord(e1, nullptr);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e != hipSuccess) st = hip_fail(e, "gather probe");
+        else *gbs = static_cast<double>(n_gathers) * row_bytes * iters / (ms * 1e-3) / 1e9;
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipFree(table); (void)hipFree(idx); (void)hipFree(sink);
+    return st;
 }
 
 mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
@@ -150,17 +237,17 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
         const int64_t vec_bytes = static_cast<int64_t>(vec) * static_cast<int64_t>(esz);
         int64_t slab_bytes = 0;
         if (opt == 0) {
-            // automatic: measured on MI355X, slabs pay (1.1-1.5x) when rows are at least 1 KB wide and one
-            // XCD's share of the table rows, at slab width, stays within a few times its 4 MB L2: 512-byte
-            // slabs when that share is at most 8 MB, else 256-byte slabs if those get it there (the
-            // 233 k x 2.4 KB table of the configs: 18.7 ms against 20.5 with 512 and 20.4 with 128), else
-            // 512-byte slabs up to 16 MB; narrower slabs or larger tables lose to the extra passes
+            // automatic: measured on MI355X, slabs pay (1.05-1.6x) when rows are at least 1 KB wide: what has to
+            // survive in L2 between two uses of a table row is then a slab of it.  512-byte slabs, except that
+            // 256-byte slabs are taken when they bring one XCD's share of the table rows within twice its 4 MB
+            // L2 and 512-byte slabs do not (the 233 k x 2.4 KB table of the configs: 18.7 ms against 20.5 with
+            // 512 and 20.4 with 128).  On tables far beyond the caches (2 M rows of 1 KB: 4.70 ms against 4.92
+            // without slabs) the gain is small but still there; narrower rows lose to the extra passes.
             const int64_t table_rows = p->n_own + static_cast<int64_t>(p->halo_gid.size());
             const int64_t class_rows = (p->xcd_min_deg > 0 ? table_rows / kXcd : table_rows) + 1;
             if (static_cast<int64_t>(dim) * static_cast<int64_t>(esz) >= 1024) {
-                if (class_rows * 512 <= (8 << 20)) slab_bytes = 512;
-                else if (class_rows * 256 <= (8 << 20)) slab_bytes = 256;
-                else if (class_rows * 512 <= (16 << 20)) slab_bytes = 512;
+                if (class_rows * 512 > (8 << 20) && class_rows * 256 <= (8 << 20)) slab_bytes = 256;
+                else slab_bytes = 512;
             }
         } else if (opt >= 64) {
             slab_bytes = opt;

@@ -337,6 +337,11 @@ mgg_status_t mgg_get_option(const char *key, int32_t *value)
     return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
 }
 
+mgg_status_t mgg_probe_gather(int64_t table_bytes, int32_t row_bytes, int64_t n_gathers, int32_t iters, uint64_t seed, double *gbytes_per_s)
+{
+    return probe_gather(table_bytes, row_bytes, n_gathers, iters, seed, gbytes_per_s);
+}
+
 mgg_status_t mgg_time_aggregate(const mgg_partition_t *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,
                                 const void *x_local, const void *x_halo, int32_t dim, int64_t ld_x, float *out,
                                 int64_t ld_out, void *stream, int32_t iters, float *ms_per_call)

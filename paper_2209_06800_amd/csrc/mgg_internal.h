@@ -35,7 +35,7 @@ struct SplitRow {
 };
 
 constexpr int kXcd = 8;             // accelerator complex dies of an MI355X, each with its own L2
-constexpr int kDefaultWpb = 4;      // work items (wavefronts) per workgroup of the aggregation kernel
+constexpr int kDefaultWpb = 2;      // work items (wavefronts) per workgroup of the aggregation kernel
 constexpr int kDefaultXcdMinDeg = 256;
 constexpr int kDefaultHotPhases = 0;        // automatic choice between hash classes and popularity phases
 constexpr int kAutoHotPhases = 4;           // phases when the automatic choice takes popularity classes
@@ -126,6 +126,7 @@ mgg_status_t launch_update_mlp(int64_t n_rows, mgg_dtype_t a_dtype, const void *
                                mgg_dtype_t w_dtype, const void *w1, const float *b1, mgg_act_t act1, const void *w2, const float *b2,
                                mgg_act_t act2, void *hidden, int64_t ld_hidden, mgg_dtype_t out_dtype, void *out, int64_t ld_out,
                                hipStream_t stream);
+mgg_status_t probe_gather(int64_t table_bytes, int32_t row_bytes, int64_t n_gathers, int32_t iters, uint64_t seed, double *gbs);
 // in place: x[i][:] = softmax(x[i][:]) for every row (update.hip)
 mgg_status_t launch_row_softmax(int64_t n_rows, int32_t d, mgg_dtype_t dtype, void *x, int64_t ld, hipStream_t stream);
 

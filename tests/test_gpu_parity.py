@@ -803,6 +803,16 @@ def test_layer_forward_in_a_hip_graph():
     part.destroy()
 
 
+def test_gather_probe_orders_the_memory_levels():
+    """The bare gather kernel behind the roofline table: rows from a table inside L2 arrive faster than
+    rows from a table in the Infinity Cache, and those faster than rows from HBM."""
+    l2 = binding.mgg_probe_gather(2 << 20, 256, n_gathers=1 << 22, iters=3)
+    mall = binding.mgg_probe_gather(64 << 20, 256, n_gathers=1 << 22, iters=3)
+    hbm = binding.mgg_probe_gather(2 << 30, 1024, n_gathers=1 << 22, iters=3)
+    assert l2 > mall > 0 and l2 > hbm > 0
+    assert l2 > 8000.0                                   # beyond the HBM peak: a cache figure
+
+
 # ----------------------------------------------------------------------------- embedding bags
 @pytest.mark.parametrize("dim,bf16,lo_hi,knobs", [(64, False, (0, 5000), {}), (16, False, (2000, 2600), dict(ps=8, dist=2)),
                                                    (128, True, (0, 20000), {}), (47, False, (0, 0), dict(xcd_min_deg=16)),

@@ -315,6 +315,16 @@ def test_binding_checks_what_the_c_abi_cannot_see():
         binding.mgg_aggregate(part, "gcn", xl, xh, out=out)
 
 
+def test_gather_probe_checks_its_arguments():
+    lib = binding.lib()
+    g = ctypes.c_double()
+    assert lib.mgg_probe_gather(1 << 20, 100, 1 << 20, 1, 1, ctypes.byref(g)) == binding.ERR_INVALID_ARG        # row size
+    assert lib.mgg_probe_gather(64, 256, 1 << 20, 1, 1, ctypes.byref(g)) == binding.ERR_INVALID_ARG             # table smaller than a row
+    assert lib.mgg_probe_gather(1 << 20, 256, 100, 1, 1, ctypes.byref(g)) == binding.ERR_INVALID_ARG            # too few gathers
+    assert lib.mgg_probe_gather(1 << 20, 256, 1 << 20, 0, 1, ctypes.byref(g)) == binding.ERR_INVALID_ARG
+    assert lib.mgg_probe_gather(1 << 20, 256, 1 << 20, 1, 1, None) == binding.ERR_INVALID_ARG
+
+
 def test_options_round_trip():
     assert binding.mgg_get_option("items_per_wave") == 0
     for v in (1, 8, 64, 0):
