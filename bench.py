@@ -158,12 +158,8 @@ def run_ablations(cfg: int, iters: int = 20):
         xh = to_dev(w.x[hg], dev, pad) if hg.size else None
         out = torch.empty((int(part.info.n_own), w.dim), dtype=torch.float32, device=dev)
         for k, v in opts.items():
-            binding.mgg_set_option(k, v)
-        try:
-            ms = min(binding.mgg_time_aggregate(part, layer.mode, xl, xh, out, eps=layer.eps, iters=iters) for _ in range(3))
-        finally:
-            for k in opts:
-                binding.mgg_set_option(k, 0)
+            part.set_option(k, v)
+        ms = min(binding.mgg_time_aggregate(part, layer.mode, xl, xh, out, eps=layer.eps, iters=iters) for _ in range(3))
         nnz = int(part.info.nnz_local + part.info.nnz_remote)
         base_ms = ms if base_ms is None else base_ms
         rows.append({"variant": name, "agg_ms": round(ms, 4), "gedges_per_s": round(nnz / ms / 1e6, 3),
@@ -471,7 +467,7 @@ def run_embedding_bags(iters: int = 20, cpu_budget_s: float = 10.0):
 
 
 def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 20.0, calibrate_copy: bool = False,
-        cold_iters: int = 5, part_id=None, split: str = "nodes"):
+        cold_iters: int = 5, part_id=None, split: str = "nodes", order_iters: int = 10):
     import torch
     from paper_2209_06800_amd import binding, inputs
 
@@ -637,6 +633,33 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
         "compulsory": comp,
     }
 
+    # Outside the timed region too: the same layers through mgg_layer_forward, in the paper's order and with
+    # MGG_ORDER_AUTO, which applies the first weight matrix before the aggregation when that narrows the rows
+    # (same values within rounding; both forms are parity-tested at full size).
+    order_ms = {}
+    if order_iters > 0:
+        for order in ("agg_first", "auto"):
+            tot = 0.0
+            xl_prev = None
+            for li, L in enumerate(layers):
+                layer = L["layer"]
+                xl = L["xl"] if li == 0 else xl_prev
+                need = binding.mgg_layer_workspace_bytes(part, layer.mode, L["ws"], layer.acts, eps=layer.eps, order=order)
+                wsp = torch.empty(need, dtype=torch.uint8, device=dev)
+                o = torch.empty_like(L["out"])
+                for _ in range(2):
+                    binding.mgg_layer_forward(part, layer.mode, xl, L["xh"], L["ws"], layer.acts, eps=layer.eps, workspace=wsp, out=o, order=order)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(order_iters):
+                    binding.mgg_layer_forward(part, layer.mode, xl, L["xh"], L["ws"], layer.acts, eps=layer.eps, workspace=wsp, out=o, order=order)
+                e1.record()
+                torch.cuda.synchronize()
+                tot += e0.elapsed_time(e1) / order_iters
+                xl_prev = o
+                del wsp
+            order_ms[order] = round(tot, 4)
+
     if verify:
         import oracle
         rng = np.random.default_rng(0)
@@ -673,6 +696,9 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "per_layer": per_layer,
+        # every layer through mgg_layer_forward: the paper's order, and the order MGG_ORDER_AUTO picks
+        "layer_forward_ms": order_ms or None,
+        "layer_forward_auto_gedges_per_s": round(nnz * len(layers) / (order_ms["auto"] * 1e-3) / 1e9, 4) if order_ms else None,
     }
     part.destroy()
     return result
@@ -696,6 +722,8 @@ def main():
                     help="run the greedy search over ps / dist / wpb (section 6) on layer 0's aggregation and exit")
     ap.add_argument("--tune-exhaustive", action="store_true",
                     help="like --tune, and measure the whole 150-point grid beside it")
+    ap.add_argument("--order-iters", type=int, default=10,
+                    help="calls of mgg_layer_forward per layer and order timed after the timed region (0 = skip)")
     ap.add_argument("--cold-iters", type=int, default=5,
                     help="aggregation launches per layer timed with cold caches after the timed region (0 = skip)")
     ap.add_argument("--split", choices=["nodes", "edges"], default="nodes",
@@ -750,7 +778,7 @@ def main():
         return
     t_begin = time.time()
     res = run(args.config or HEADLINE_CONFIG, args.steps, args.warmup, args.verify, args.cpu_seconds, args.calibrate_copy,
-              args.cold_iters, args.part_id, args.split)
+              args.cold_iters, args.part_id, args.split, args.order_iters)
     if args.config is None:
         # the other configs, same protocol, without the CPU leg; each adds its per-layer and roofline figures
         others = []
@@ -758,8 +786,9 @@ def main():
             if time.time() - t_begin > args.time_budget:
                 log(f"[bench] time budget reached: config {cfg} not run")
                 continue
-            r = run(cfg, args.steps, args.warmup, args.verify, 0.0, False, args.cold_iters, None, "nodes")
-            others.append({k: r[k] for k in ("value", "unit", "ms_per_step", "steps", "dtype", "config", "roofline", "per_layer")})
+            r = run(cfg, args.steps, args.warmup, args.verify, 0.0, False, args.cold_iters, None, "nodes", args.order_iters)
+            others.append({k: r[k] for k in ("value", "unit", "ms_per_step", "steps", "dtype", "config", "roofline", "per_layer",
+                                             "layer_forward_ms", "layer_forward_auto_gedges_per_s")})
         res["other_configs"] = others
     print(json.dumps(res), flush=True)
 

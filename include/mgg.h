@@ -370,20 +370,26 @@ mgg_status_t mgg_tune_aggregate(int64_t num_nodes, const int64_t *row_ptr, const
                                 int64_t ld_x, float *out, int64_t ld_out, void *stream, int32_t iters,
                                 mgg_tuner_t *tuner, mgg_knobs_t *best, double *best_ms);
 
-/* Run-time switches for experiments (ablations of section 7.2's kind).  Known keys:
+/* Run-time switches for experiments (ablations of section 7.2's kind).  The switches of the aggregation
+ * belong to a partition: mgg_partition_set_option changes them for that partition only (not while a call
+ * using it is running on another thread).  mgg_set_option sets the process-wide default that partitions
+ * built afterwards start from -- existing partitions keep what they have -- and the one switch of the
+ * Update kernels, which have no handle to carry it.  Keys:
  *   "lds_halo"    0/1  stage halo rows through LDS ahead of accumulation  (default 0)
  *   "split_phases" 0/1 aggregate the local lists and the remote lists in two launches, the
  *                      second adding to the first (no interleaving; default 0)
- *   "update_stream" 0/1 the Update kernels added for streaming efficiency (whole-line kernels, the
- *                      one-kernel MLP, two W slabs in LDS) are used where they apply (default 1;
- *                      0 = the plain register-resident and slab kernels everywhere)
  *   "col_slab_bytes"   0 = automatic (default), 1 = off, or a power of two in [64, 4096]:
  *                      bytes of an embedding row handled per pass over the work items
  *   "items_per_wave"   0 = automatic (default), or 1..64: work items a wavefront takes one after
  *                      the other, the next one's ids and descriptor requested while it gathers
- * Unknown key or bad value -> MGG_ERR_INVALID_ARG.  Not thread-safe against running calls. */
+ *   "update_stream" 0/1 (process-wide only) the Update kernels added for streaming efficiency (whole-line
+ *                      kernels, the one-kernel MLP, two W slabs in LDS) are used where they apply
+ *                      (default 1; 0 = the plain register-resident and slab kernels everywhere)
+ * Unknown key or bad value -> MGG_ERR_INVALID_ARG. */
 mgg_status_t mgg_set_option(const char *key, int32_t value);
 mgg_status_t mgg_get_option(const char *key, int32_t *value);
+mgg_status_t mgg_partition_set_option(mgg_partition_t *p, const char *key, int32_t value);
+mgg_status_t mgg_partition_get_option(const mgg_partition_t *p, const char *key, int32_t *value);
 
 /* Time of the most recent kernel launches of this thread is not kept by the library; for
  * measurement the caller brackets calls with events on its stream.  This helper does that

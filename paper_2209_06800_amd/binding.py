@@ -28,7 +28,7 @@ _STATUS_NAME = ["OK", "INVALID_ARG", "BAD_GRAPH", "UNSUPPORTED", "ALLOC", "HIP"]
 EXPORTED_SYMBOLS = [
     "mgg_build_partition", "mgg_partition_info", "mgg_partition_export", "mgg_partition_destroy",
     "mgg_partition_reserve", "mgg_aggregate_scratch_bytes", "mgg_aggregate", "mgg_aggregate_static", "mgg_aggregate_to", "mgg_build_bags", "mgg_bag_sum", "mgg_update", "mgg_update_mlp", "mgg_layer_workspace_bytes", "mgg_layer_forward",
-    "mgg_split_edge_balanced", "mgg_set_option", "mgg_get_option", "mgg_time_aggregate", "mgg_probe_gather",
+    "mgg_split_edge_balanced", "mgg_set_option", "mgg_get_option", "mgg_partition_set_option", "mgg_partition_get_option", "mgg_time_aggregate", "mgg_probe_gather",
     "mgg_model_evaluate", "mgg_tuner_create", "mgg_tuner_set_constraint", "mgg_tuner_next", "mgg_tuner_report", "mgg_tuner_result",
     "mgg_tuner_table", "mgg_tuner_destroy", "mgg_tune_aggregate",
     "mgg_last_error", "mgg_version",
@@ -135,6 +135,8 @@ def lib():
         L.mgg_split_edge_balanced.argtypes = [C.c_int64, C.c_void_p, C.c_int32, C.c_void_p]
         L.mgg_set_option.argtypes = [C.c_char_p, C.c_int32]
         L.mgg_get_option.argtypes = [C.c_char_p, C.POINTER(C.c_int32)]
+        L.mgg_partition_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int32]
+        L.mgg_partition_get_option.argtypes = [C.c_void_p, C.c_char_p, C.POINTER(C.c_int32)]
         L.mgg_time_aggregate.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p,
                                          C.c_int32, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                                          C.POINTER(C.c_float)]
@@ -233,6 +235,15 @@ class Partition:
         if dim > self._reserved:
             _check(lib().mgg_partition_reserve(self.handle, int(dim)))
             self._reserved = int(dim)
+
+    def set_option(self, key: str, value: int):
+        """A run-time switch of this partition's aggregations (mgg_partition_set_option)."""
+        _check(lib().mgg_partition_set_option(self.handle, key.encode(), int(value)))
+
+    def get_option(self, key: str) -> int:
+        v = C.c_int32()
+        _check(lib().mgg_partition_get_option(self.handle, key.encode(), C.byref(v)))
+        return v.value
 
     def export(self) -> dict:
         """Copy every integer structure to numpy arrays (for bit-exact checks)."""

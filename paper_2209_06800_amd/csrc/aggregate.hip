@@ -233,7 +233,7 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
     // disjoint, so nothing has to be combined.
     int slab_vecs = nvec;
     {
-        const int64_t opt = option_col_slab_bytes();
+        const int64_t opt = p->opt_col_slab_bytes;
         const int64_t vec_bytes = static_cast<int64_t>(vec) * static_cast<int64_t>(esz);
         int64_t slab_bytes = 0;
         if (opt == 0) {
@@ -299,7 +299,7 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
     const int64_t n_groups = (a.n_items + wpb - 1) / wpb;
     const int64_t short_groups = (a.n_short + 64 / lpr - 1) / (64 / lpr);
     {
-        const int32_t opt = option_items_per_wave();
+        const int32_t opt = p->opt_items_per_wave;
         auto pick = [&](int64_t units) { return static_cast<int32_t>(opt > 0 ? opt : std::min<int64_t>(8, std::max<int64_t>(1, units * n_slabs / 8192))); };
         a.items_per_wave = pick(n_groups);
         a.short_per_wave = pick((short_groups + wpb - 1) / wpb);
@@ -327,14 +327,14 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
 
     // one launch for both neighbour lists (the default), or -- as the ablation of interleaving --
     // the local lists first and the remote lists in a second launch that adds to the result
-    const bool two_phases = option_split_phases() != 0 && !p->halo_gid.empty() && !a.out_bf16;   // phase 2 reads `out` back
+    const bool two_phases = p->opt_split_phases != 0 && !p->halo_gid.empty() && !a.out_bf16;   // phase 2 reads `out` back
     for (int phase = two_phases ? 1 : 0; phase <= (two_phases ? 2 : 0); ++phase) {
         a.phase = phase;
         const int64_t short_waves = (short_groups + a.short_per_wave - 1) / a.short_per_wave;
         int grid_x = a.n_item_blocks + static_cast<int>((short_waves + wpb - 1) / wpb);
         if (n_slabs > 1) grid_x = (grid_x + kXcd - 1) / kXcd * kXcd;   // keeps workgroup x on XCD x mod 8 in every slab
         const dim3 grid(static_cast<unsigned>(grid_x), static_cast<unsigned>(n_slabs));
-        const bool lds = option_lds_halo() != 0 && !p->halo_gid.empty();
+        const bool lds = p->opt_lds_halo != 0 && !p->halo_gid.empty();
         if (grid_x > 0) {
             hipError_t e;
             if (bf16) e = launch_aggregate_bf16(a, gcn, vec, grid, wpb, stream, lpr, ch, lds);

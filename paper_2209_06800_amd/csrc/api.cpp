@@ -18,6 +18,29 @@ int32_t option_split_phases() { return g_split_phases.load(); }
 int32_t option_update_stream() { return g_update_stream.load(); }
 int32_t option_items_per_wave() { return g_items_per_wave.load(); }
 
+void take_default_options(mgg_partition *p)
+{
+    p->opt_lds_halo = g_lds_halo.load(); p->opt_col_slab_bytes = g_col_slab_bytes.load();
+    p->opt_split_phases = g_split_phases.load(); p->opt_items_per_wave = g_items_per_wave.load();
+}
+
+mgg_status_t check_option(const char *key, int32_t value)
+{
+    if (!key) return fail(MGG_ERR_INVALID_ARG, "key is NULL");
+    if (!std::strcmp(key, "col_slab_bytes")) {
+        // 0: automatic, 1: off, otherwise a power of two between 64 and 4096
+        if (value != 0 && value != 1 && (value < 64 || value > 4096 || (value & (value - 1)))) return fail(MGG_ERR_INVALID_ARG, "col_slab_bytes must be 0, 1 or a power of two in [64, 4096]");
+        return MGG_OK;
+    }
+    if (!std::strcmp(key, "items_per_wave")) {
+        if (value < 0 || value > 64) return fail(MGG_ERR_INVALID_ARG, "items_per_wave must be 0 (automatic) or 1..64");
+        return MGG_OK;
+    }
+    if (std::strcmp(key, "lds_halo") && std::strcmp(key, "split_phases") && std::strcmp(key, "update_stream")) return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
+    if (value != 0 && value != 1) return fail(MGG_ERR_INVALID_ARG, "option value must be 0 or 1");
+    return MGG_OK;
+}
+
 static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline bool dtype_ok(mgg_dtype_t t) { return t == MGG_F32 || t == MGG_BF16; }
 
@@ -307,23 +330,14 @@ mgg_status_t mgg_update_mlp(int64_t n_rows, mgg_dtype_t a_dtype, const void *a, 
 
 mgg_status_t mgg_set_option(const char *key, int32_t value)
 {
-    if (!key) return fail(MGG_ERR_INVALID_ARG, "key is NULL");
-    if (!std::strcmp(key, "col_slab_bytes")) {
-        // 0: automatic, 1: off, otherwise a power of two between 64 and 4096
-        if (value != 0 && value != 1 && (value < 64 || value > 4096 || (value & (value - 1)))) return fail(MGG_ERR_INVALID_ARG, "col_slab_bytes must be 0, 1 or a power of two in [64, 4096]");
-        g_col_slab_bytes = value;
-        return MGG_OK;
-    }
-    if (!std::strcmp(key, "items_per_wave")) {
-        if (value < 0 || value > 64) return fail(MGG_ERR_INVALID_ARG, "items_per_wave must be 0 (automatic) or 1..64");
-        g_items_per_wave = value;
-        return MGG_OK;
-    }
-    if (value != 0 && value != 1) return fail(MGG_ERR_INVALID_ARG, "option value must be 0 or 1");
-    if (!std::strcmp(key, "lds_halo")) { g_lds_halo = value; return MGG_OK; }
-    if (!std::strcmp(key, "split_phases")) { g_split_phases = value; return MGG_OK; }
-    if (!std::strcmp(key, "update_stream")) { g_update_stream = value; return MGG_OK; }
-    return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
+    mgg_status_t s = check_option(key, value);
+    if (s != MGG_OK) return s;
+    if (!std::strcmp(key, "col_slab_bytes")) g_col_slab_bytes = value;
+    else if (!std::strcmp(key, "items_per_wave")) g_items_per_wave = value;
+    else if (!std::strcmp(key, "lds_halo")) g_lds_halo = value;
+    else if (!std::strcmp(key, "split_phases")) g_split_phases = value;
+    else g_update_stream = value;
+    return MGG_OK;
 }
 
 mgg_status_t mgg_get_option(const char *key, int32_t *value)
@@ -334,6 +348,29 @@ mgg_status_t mgg_get_option(const char *key, int32_t *value)
     if (!std::strcmp(key, "split_phases")) { *value = g_split_phases; return MGG_OK; }
     if (!std::strcmp(key, "update_stream")) { *value = g_update_stream; return MGG_OK; }
     if (!std::strcmp(key, "items_per_wave")) { *value = g_items_per_wave; return MGG_OK; }
+    return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
+}
+
+mgg_status_t mgg_partition_set_option(mgg_partition_t *p, const char *key, int32_t value)
+{
+    if (!p) return fail(MGG_ERR_INVALID_ARG, "partition is NULL");
+    mgg_status_t s = check_option(key, value);
+    if (s != MGG_OK) return s;
+    if (!std::strcmp(key, "col_slab_bytes")) p->opt_col_slab_bytes = value;
+    else if (!std::strcmp(key, "items_per_wave")) p->opt_items_per_wave = value;
+    else if (!std::strcmp(key, "lds_halo")) p->opt_lds_halo = value;
+    else if (!std::strcmp(key, "split_phases")) p->opt_split_phases = value;
+    else return fail(MGG_ERR_INVALID_ARG, "'%s' is not a switch of the aggregation", key);
+    return MGG_OK;
+}
+
+mgg_status_t mgg_partition_get_option(const mgg_partition_t *p, const char *key, int32_t *value)
+{
+    if (!p || !key || !value) return fail(MGG_ERR_INVALID_ARG, "NULL argument");
+    if (!std::strcmp(key, "lds_halo")) { *value = p->opt_lds_halo; return MGG_OK; }
+    if (!std::strcmp(key, "col_slab_bytes")) { *value = p->opt_col_slab_bytes; return MGG_OK; }
+    if (!std::strcmp(key, "split_phases")) { *value = p->opt_split_phases; return MGG_OK; }
+    if (!std::strcmp(key, "items_per_wave")) { *value = p->opt_items_per_wave; return MGG_OK; }
     return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
 }
 

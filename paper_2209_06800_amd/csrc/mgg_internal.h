@@ -78,6 +78,8 @@ struct mgg_partition {
     std::vector<mgg::WorkItem> items;
     std::vector<mgg::SplitRow> split_rows;
     int64_t n_split_items = 0;
+    // run-time switches of this partition's aggregations: the process-wide defaults at build time, then mgg_partition_set_option
+    int32_t opt_lds_halo = 0, opt_col_slab_bytes = 0, opt_split_phases = 0, opt_items_per_wave = 0;
     int32_t reserved_dim = 0;         // widest aggregation the partition's own scratch buffer was sized for
     int64_t n_groups_local = 0, n_groups_remote = 0;
     mgg::DeviceArrays d;          // device copies; d.scratch is sized by mgg_partition_reserve (or at build)
@@ -99,6 +101,8 @@ int32_t option_col_slab_bytes();
 int32_t option_split_phases();
 int32_t option_update_stream();
 int32_t option_items_per_wave();
+void take_default_options(mgg_partition *p);      // copies the four process-wide defaults above into a new partition
+mgg_status_t check_option(const char *key, int32_t value);   // range check shared by both setters
 
 // kernels (aggregate.hip / update.hip)
 mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps, mgg_dtype_t x_dtype,

@@ -392,6 +392,7 @@ mgg_status_t mgg_build_partition(int64_t num_nodes, const int64_t *row_ptr, cons
     mgg_partition *p = new (std::nothrow) mgg_partition;
     if (!p) return fail(MGG_ERR_ALLOC, "out of host memory");
     try {
+        take_default_options(p);
         p->num_nodes = num_nodes; p->lb = lb; p->ub = ub; p->n_own = n_own; p->n_local_rows = n_own;
         p->num_parts = num_parts; p->part_id = part_id;
 
@@ -496,6 +497,7 @@ mgg_status_t mgg_build_bags(int64_t num_bags, const int64_t *bag_ptr, const int3
     mgg_partition *p = new (std::nothrow) mgg_partition;
     if (!p) return fail(MGG_ERR_ALLOC, "out of host memory");
     try {
+        take_default_options(p);
         p->bags = true;
         p->num_nodes = table_rows; p->lb = local_lo; p->ub = local_hi; p->n_own = num_bags; p->n_local_rows = local_hi - local_lo;
         p->num_parts = 1; p->part_id = 0;

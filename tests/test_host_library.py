@@ -315,6 +315,31 @@ def test_binding_checks_what_the_c_abi_cannot_see():
         binding.mgg_aggregate(part, "gcn", xl, xh, out=out)
 
 
+def test_aggregation_switches_belong_to_a_partition():
+    """mgg_set_option sets the defaults new partitions start from; mgg_partition_set_option changes one
+    partition and no other."""
+    rp, col = np.array([0, 1, 2]), np.array([1, 0], dtype=np.int32)
+    a = binding.mgg_build_partition(rp, col, host_only=True)
+    binding.mgg_set_option("col_slab_bytes", 128)
+    binding.mgg_set_option("items_per_wave", 3)
+    try:
+        b = binding.mgg_build_partition(rp, col, host_only=True)
+    finally:
+        binding.mgg_set_option("col_slab_bytes", 0)
+        binding.mgg_set_option("items_per_wave", 0)
+    assert (a.get_option("col_slab_bytes"), a.get_option("items_per_wave")) == (0, 0)        # built before: untouched
+    assert (b.get_option("col_slab_bytes"), b.get_option("items_per_wave")) == (128, 3)
+    a.set_option("lds_halo", 1)
+    a.set_option("split_phases", 1)
+    assert a.get_option("lds_halo") == 1 and b.get_option("lds_halo") == 0 and binding.mgg_get_option("lds_halo") == 0
+    for key, bad in (("col_slab_bytes", 96), ("items_per_wave", 65), ("lds_halo", 2), ("update_stream", 1), ("nope", 0)):
+        assert _status(a.set_option, key, bad) == binding.ERR_INVALID_ARG
+    with pytest.raises(MggError):
+        a.get_option("update_stream")
+    lib = binding.lib()
+    assert lib.mgg_partition_set_option(None, b"lds_halo", 1) == binding.ERR_INVALID_ARG
+
+
 def test_gather_probe_checks_its_arguments():
     lib = binding.lib()
     g = ctypes.c_double()
