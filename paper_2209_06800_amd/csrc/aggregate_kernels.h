@@ -34,7 +34,7 @@ namespace mgg {
 constexpr int kWave = 64;
 constexpr int kMaxWpb = 16;         // wavefronts per workgroup of the aggregation kernel
 constexpr int kStageSlots = 8;      // LDS-staged variant: load instructions (1 KB each) per wavefront stage
-constexpr int kStageWpb = 4;        // LDS-staged variant: most wavefronts per workgroup (a wavefront owns 2 stages of 8 KB)
+constexpr int kStageWpb = 8;        // LDS-staged variant: most wavefronts per workgroup (a wavefront owns 2 stages of 8 KB)
 
 struct AggArgs {
     const int32_t *local_row_ptr, *local_col, *remote_row_ptr, *remote_col;
@@ -466,7 +466,7 @@ __device__ __forceinline__ void gather_pair(Acc<K> &acc, const char *xl, const c
 template <class K, bool GCN, bool LDSH>
 __global__ __launch_bounds__(kWave * kMaxWpb) void aggregate_kernel(const AggArgs a)
 {
-    __shared__ uint4 stage_all[LDSH ? kStageWpb : 1][LDSH ? 2 : 1][LDSH ? kStageSlots : 1][LDSH ? kWave : 1];
+    extern __shared__ uint4 stage_all[];        // LDS-staged variant: two stages of kStageSlots load instructions per wavefront
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) / kWave);
     const int wpb = static_cast<int>(blockDim.x) / kWave;   // wavefronts per workgroup
@@ -528,7 +528,7 @@ __global__ __launch_bounds__(kWave * kMaxWpb) void aggregate_kernel(const AggArg
                     } else if constexpr (LDSH) {
                         // remote rows travel into LDS one batch ahead of their accumulation; the local partition
                         // of the pair is gathered through registers while the first batch is in flight
-                        uint4 (*stage)[kStageSlots][kWave] = stage_all[wave];
+                        uint4 (*stage)[kStageSlots][kWave] = reinterpret_cast<uint4 (*)[kStageSlots][kWave]>(stage_all + static_cast<size_t>(wave) * 2 * kStageSlots * kWave);
                         uint32_t lo_l, lo_r, hi;
                         row_offset<false>(idx_l, ldb, lo_l, hi);
                         row_offset<false>(idx_r, ldb, lo_r, hi);
@@ -674,8 +674,9 @@ hipError_t launch_cfg(const AggArgs &a, bool gcn, dim3 grid, int wpb, hipStream_
 {
     if constexpr (K::CH == 1 && sizeof(typename K::raw) == 16) {
         if (lds_halo && wpb <= kStageWpb && !a.wide) {
-            if (gcn) hipLaunchKernelGGL((aggregate_kernel<K, true, true>), grid, dim3(kWave * wpb), 0, stream, a);
-            else hipLaunchKernelGGL((aggregate_kernel<K, false, true>), grid, dim3(kWave * wpb), 0, stream, a);
+            const size_t lds = static_cast<size_t>(wpb) * 2 * kStageSlots * kWave * sizeof(uint4);     // 16 KB per wavefront
+            if (gcn) hipLaunchKernelGGL((aggregate_kernel<K, true, true>), grid, dim3(kWave * wpb), lds, stream, a);
+            else hipLaunchKernelGGL((aggregate_kernel<K, false, true>), grid, dim3(kWave * wpb), lds, stream, a);
             return hipGetLastError();
         }
     }

@@ -170,6 +170,20 @@ def test_padded_rows_and_unaligned_base(ld_pad, misalign):
     check_aggregate(row_ptr, col, 2, 0, bounds, xb, "gin", ld_pad=ld_pad, misalign=misalign, what="bf16 padded")
 
 
+def test_tables_beyond_4gb_take_64_bit_row_offsets():
+    """Row offsets inside a table are 32-bit unless a table reaches beyond 4 GB; rows spaced 2.1 MB apart
+    put a 2048-row table there (work items, short rows and the self term all use the wide path)."""
+    row_ptr, col, rng = small_rmat(seed=41)
+    n = row_ptr.size - 1
+    x = rng.standard_normal((n, 64)).astype(np.float32)
+    bounds = inputs.equal_node_bounds(n, 2)
+    ld = (1 << 32) // (4 * (n // 2)) + 1024                  # rows * ld * 4 bytes just beyond 2^32
+    assert (n // 2) * ld * 4 >= 1 << 32
+    for mode in ("gcn", "gin"):
+        check_aggregate(row_ptr, col, 2, 1, bounds, x, mode, eps=0.5, ld_pad=ld - 64, what=f"wide offsets {mode}")
+    torch.cuda.empty_cache()
+
+
 def test_degenerate_graphs():
     rng = np.random.default_rng(3)
     # no edges at all: every row is its own embedding (times 1 + eps for GIN)
