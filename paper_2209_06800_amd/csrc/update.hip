@@ -102,15 +102,20 @@ __global__ __launch_bounds__(kThreads) void update_f32_kernel(const UpdArgs p)
     store_tiles<NT>(p, acc, m0, n0, lane);
 }
 
-// The same tile with two W slabs in LDS: the next slab travels from global memory into registers
-// while the current one is multiplied and is written to the other buffer afterwards, so a K slab
-// costs one barrier and the load latency of W is off the critical path.  For weight matrices whose
-// rows allow 16-byte loads and whose width is a whole number of workgroup tiles.
+// The same tile with two W slabs in LDS and workgroups that stay: the grid is sized to the chip and a
+// workgroup walks over row tiles.  (tile, K slab) pairs form one sequence; while one pair is multiplied
+// the next pair's W slab travels from global memory straight into the other LDS buffer and its A
+// fragment into registers -- also across the end of a tile, so the stores of a finished tile and the
+// first loads of the next one overlap with MFMAs instead of ending and starting a workgroup.  A slab
+// costs one barrier.  For weight matrices whose rows allow 16-byte loads and whose width is a whole
+// number of workgroup tiles.
 extern __shared__ __attribute__((aligned(16))) unsigned char w_db[];
+typedef const __attribute__((address_space(1))) void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
 
 template <int NT, int WN>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void update_f32_db_kernel(const UpdArgs p)
+void update_f32_db_kernel(const UpdArgs p, int64_t n_tiles)
 {
     constexpr int BK = 32, NC = NT * 32 * WN, WM = kWaves / WN;
     constexpr int UNITS = BK * NC / 4 / kThreads;          // 16-byte pieces of a W slab per thread
@@ -118,70 +123,101 @@ void update_f32_db_kernel(const UpdArgs p)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 31, h = lane >> 5;
     const int wm = wave / WN, wn = wave % WN;
-    const int64_t m0 = (static_cast<int64_t>(blockIdx.x) * WM + wm) * 32;
     const int nb = blockIdx.y * NC;
     const int n0 = nb + wn * NT * 32;
     const float *W = static_cast<const float *>(p.w);
-    const int64_t row = m0 + i < p.n_rows ? m0 + i : p.n_rows - 1;
-    const float *arow = static_cast<const float *>(p.a) + row * p.ld_a;
+    const int n_slabs = (p.d_in + BK - 1) / BK;
+    auto tile_rows = [&](int64_t tile, int64_t &m0) -> const float * {
+        m0 = (tile * WM + wm) * 32;
+        const int64_t row = m0 + i < p.n_rows ? m0 + i : p.n_rows - 1;     // rows past the end: a valid row, never stored
+        return static_cast<const float *>(p.a) + row * p.ld_a;
+    };
 
-    float4 wreg[UNITS];
-    auto load_w = [&](int k_begin) {
+    // A W slab travels from global memory straight into LDS (global_load_lds, 16 bytes per lane): piece
+    // id = u * kThreads + thread sits at float4 index id of the buffer, which is where lane `lane` of a
+    // wave-wide load based at the wavefront's first piece lands.  Rows of the slab past d_in are written
+    // as zeros by the lanes that would have loaded them.
+    auto stage_w = [&](int k_begin, float *buf) {
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
-            const int id = u * kThreads + threadIdx.x, kk = id / (NC / 4), n4 = id % (NC / 4);
-            wreg[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k_begin + kk < p.d_in) wreg[u] = *reinterpret_cast<const float4 *>(W + static_cast<int64_t>(k_begin + kk) * p.d_out + nb + 4 * n4);
+            const int id0 = u * kThreads + wave * kWave;                 // first piece of this wavefront
+            const int id = id0 + lane, kk = id / (NC / 4), n4 = id % (NC / 4);
+            if (k_begin + kk < p.d_in) {
+                const float *src = W + static_cast<int64_t>(k_begin + kk) * p.d_out + nb + 4 * n4;
+                __builtin_amdgcn_global_load_lds((gptr_t)(const void *)src, (lptr_t)(void *)(reinterpret_cast<float4 *>(buf) + id0), 16, 0, 0);
+            } else {
+                reinterpret_cast<float4 *>(buf)[id] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
         }
     };
-    auto store_w = [&](float *buf) {
-#pragma unroll
-        for (int u = 0; u < UNITS; ++u) reinterpret_cast<float4 *>(buf)[u * kThreads + threadIdx.x] = wreg[u];
-    };
 
-    f32x16 acc[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-
+    int64_t tile = blockIdx.x, m0;                           // the host launches at most n_tiles workgroups
+    const float *arow = tile_rows(tile, m0);
     float af[16], an[16];
-    load_w(0);
+    stage_w(0, w_lds);
     load_a_f32(p, arow, 16 * h, BK, af);
-    store_w(w_lds);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // the slab has landed in LDS
     __syncthreads();
     int cur = 0;
 #pragma unroll 1
-    for (int k0 = 0; k0 < p.d_in; k0 += BK) {
-        const bool more = k0 + BK < p.d_in;                  // uniform over the workgroup
-        if (more) {
-            load_w(k0 + BK);
-            load_a_f32(p, arow, k0 + BK + 16 * h, k0 + 2 * BK, an);
-        }
-        // W fragments are read from LDS one MFMA group ahead, so that the matrix pipe never waits for them
-        const float *wbuf = w_lds + cur * (BK * NC) + (16 * h) * NC + wn * NT * 32 + i;
-        float wf[2][NT];
+    for (;;) {
+        f32x16 acc[NT];
 #pragma unroll
-        for (int t = 0; t < NT; ++t) wf[0][t] = wbuf[t * 32];
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int c = 0; c < 16; ++c) {
-            if (c + 1 < 16) {
-#pragma unroll
-                for (int t = 0; t < NT; ++t) wf[(c + 1) & 1][t] = wbuf[(c + 1) * NC + t * 32];
+            for (int q = 0; q < 16; ++q) acc[t][q] = 0.f;
+        const int64_t ntile = tile + gridDim.x;
+        int64_t nm0 = m0;
+        const float *narow = arow;
+#pragma unroll 1
+        for (int ks = 0; ks < n_slabs; ++ks) {
+            // the pair after this one (all of this is uniform over the workgroup)
+            const bool last_slab = ks + 1 == n_slabs;
+            const bool more = !last_slab || ntile < n_tiles;
+            const int nks = last_slab ? 0 : ks + 1;
+            if (more) {
+                if (last_slab) narow = tile_rows(ntile, nm0);
+                stage_w(nks * BK, w_lds + (cur ^ 1) * (BK * NC));   // the other buffer: nobody reads it before the barrier below
+                load_a_f32(p, narow, nks * BK + 16 * h, (nks + 1) * BK, an);
             }
+            // W fragments are read from LDS one MFMA group ahead, so that the matrix pipe never waits for them.
+            // MFMA number c contracts k0 + c and k0 + 16 + c: in the last slab the steps whose first k is
+            // past d_in add nothing and are left out, four at a time.
+            const int n_c = p.d_in - ks * BK;
+            const float *wbuf = w_lds + cur * (BK * NC) + (16 * h) * NC + wn * NT * 32 + i;
+            float wf[2][NT];
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[c & 1][t], af[c], acc[t], 0, 0, 0);
-        }
-        if (more) {
-            store_w(w_lds + (cur ^ 1) * (BK * NC));
+            for (int t = 0; t < NT; ++t) wf[0][t] = wbuf[t * 32];
 #pragma unroll
-            for (int c = 0; c < 16; ++c) af[c] = an[c];
+            for (int c = 0; c < 16; ++c) {
+                if (c + 1 < 16) {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) wf[(c + 1) & 1][t] = wbuf[(c + 1) * NC + t * 32];
+                }
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[c & 1][t], af[c], acc[t], 0, 0, 0);
+                if ((c & 3) == 3 && c + 1 < 16 && c + 1 >= n_c) break;
+            }
+            if (more) {
+#pragma unroll
+                for (int c = 0; c < 16; ++c) af[c] = an[c];
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the next slab has landed in LDS
+            __syncthreads();
+            cur ^= 1;
         }
-        __syncthreads();
-        cur ^= 1;
+        // the stores leave while the next tile's first slab is multiplied; the wait one slab later is the
+        // first that includes them
+        // the output and bias pointers are made opaque per tile: what depends only on them and on the lane
+        // (an address per output vector, the bias values) would otherwise be computed once ahead of all
+        // loops and held in registers the accumulators need
+        UpdArgs ps = p;
+        asm volatile("" : "+s"(ps.out), "+s"(ps.bias), "+s"(ps.d_out));       // (d_out: a lane mask per column test)
+        store_tiles<NT>(ps, acc, m0, n0, lane);
+        if (ntile >= n_tiles) break;
+        tile = ntile; m0 = nm0; arow = narow;
     }
-    store_tiles<NT>(p, acc, m0, n0, lane);
 }
 
 // ---- bf16 weights: v_mfma_f32_32x32x16_bf16 -------------------------------------------------
@@ -554,14 +590,31 @@ hipError_t launch_resident(const UpdArgs &p, bool w_bf16, bool a_bf16, int block
 }
 
 template <int NT, int WN>
-hipError_t launch_shape(const UpdArgs &p, bool w_bf16, bool a_bf16, dim3 grid, hipStream_t s)
+hipError_t launch_shape(const UpdArgs &p, bool w_bf16, bool a_bf16, dim3 grid, int cus, hipStream_t s)
 {
     if (!w_bf16 && p.w_vec_ok && p.d_out % (NT * 32 * WN) == 0 && option_update_stream() != 0) {
         constexpr int lds_bytes = 2 * 32 * NT * 32 * WN * 4;
-        // up to 64 KB of dynamic LDS: ask for it (cheap, so done at every launch rather than remembered)
-        if (lds_bytes > 48 * 1024)
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&update_f32_db_kernel<NT, WN>), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        hipLaunchKernelGGL((update_f32_db_kernel<NT, WN>), grid, dim3(kThreads), lds_bytes, s, p);
+        // Short contractions (d_in <= 256: at most 8 slabs): as many workgroups as the chip holds at once (two
+        // per CU: 64 KB of LDS each, two wavefronts per SIMD), each walking over row tiles, so that a tile's
+        // stores and the next tile's first loads hide behind MFMAs (100 -> 256: 227 -> 202 us).  Long ones:
+        // a workgroup per tile, handed out by the dispatcher as CUs free up (602 -> 256: 693 us, 706 us when
+        // the tiles are dealt out ahead of time).
+        const int64_t slots = p.d_in <= 256 ? 2 * static_cast<int64_t>(cus) : INT64_MAX;
+        if constexpr (NT == 4 && WN == 2) {
+            // 256 columns: one wavefront per 32 rows x 256 columns, so that every row of A is read by one
+            // wavefront only (two side by side, each reading the rows, measured 6 % slower on 602 -> 256)
+            const int64_t n_tiles = (p.n_rows + 32 * kWaves - 1) / (32 * kWaves);
+            grid.x = static_cast<unsigned>(n_tiles < slots ? n_tiles : slots);
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&update_f32_db_kernel<8, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            hipLaunchKernelGGL((update_f32_db_kernel<8, 1>), grid, dim3(kThreads), lds_bytes, s, p, n_tiles);
+        } else {
+            const int64_t n_tiles = (p.n_rows + 32 * (kWaves / WN) - 1) / (32 * (kWaves / WN));
+            grid.x = static_cast<unsigned>(n_tiles < slots ? n_tiles : slots);
+            // up to 64 KB of dynamic LDS: ask for it (cheap, so done at every launch rather than remembered)
+            if (lds_bytes > 48 * 1024)
+                (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&update_f32_db_kernel<NT, WN>), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            hipLaunchKernelGGL((update_f32_db_kernel<NT, WN>), grid, dim3(kThreads), lds_bytes, s, p, n_tiles);
+        }
     }
     else if (!w_bf16) hipLaunchKernelGGL((update_f32_kernel<NT, WN>), grid, dim3(kThreads), 0, s, p);
     else if (a_bf16) hipLaunchKernelGGL((update_bf16_kernel<NT, WN, true>), grid, dim3(kThreads), 0, s, p);
@@ -687,10 +740,10 @@ static mgg_status_t launch_update_gemm(int64_t n_rows, mgg_dtype_t a_dtype, cons
     if (gx > INT32_MAX) return fail(MGG_ERR_UNSUPPORTED, "too many rows for one launch");
     dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>((d_out + nc - 1) / nc));
     hipError_t e;
-    if (nt == 1) e = launch_shape<1, 1>(p, w_bf16, a_bf16, grid, stream);
-    else if (nt == 2) e = launch_shape<2, 1>(p, w_bf16, a_bf16, grid, stream);
-    else if (wn == 1) e = launch_shape<4, 1>(p, w_bf16, a_bf16, grid, stream);
-    else e = launch_shape<4, 2>(p, w_bf16, a_bf16, grid, stream);
+    if (wn == 2) e = launch_shape<4, 2>(p, w_bf16, a_bf16, grid, cus, stream);
+    else if (nt == 1) e = launch_shape<1, 1>(p, w_bf16, a_bf16, grid, cus, stream);
+    else if (nt == 2) e = launch_shape<2, 1>(p, w_bf16, a_bf16, grid, cus, stream);
+    else e = launch_shape<4, 1>(p, w_bf16, a_bf16, grid, cus, stream);
     if (e != hipSuccess) return hip_fail(e, "update kernel launch");
     return MGG_OK;
 }
