@@ -144,6 +144,10 @@ struct Cfg {
     static constexpr int VEC = VEC_, LPR = LPR_, CH = CH_;
     static constexpr int NPW = kWave / LPR;                 // neighbour rows per load instruction
     static constexpr int U = (MGG_AGG_INFLIGHT / CH) > 0 ? (MGG_AGG_INFLIGHT / CH) : 1;   // neighbour rows in flight per lane
+    // Wavefronts per SIMD the register allocation must allow.  The workgroup limit (16 wavefronts) gives 4;
+    // the 256-byte fp32 variant sits one register above the budget of 5 and loses nothing when held to it
+    // (2 % faster on the 602-column workload); the others would spill.
+    static constexpr int MIN_WAVES = (!BF16_ && VEC_ == 4 && LPR_ == 16 && CH_ == 1) ? 5 : 4;
     using elem = typename std::conditional<BF16, uint16_t, float>::type;
     using raw = typename Raw<BF16, VEC>::type;
     static constexpr int VEC_BYTES = static_cast<int>(sizeof(raw));
@@ -464,7 +468,7 @@ __device__ __forceinline__ void gather_pair(Acc<K> &acc, const char *xl, const c
 }
 
 template <class K, bool GCN, bool LDSH>
-__global__ __launch_bounds__(kWave * kMaxWpb) void aggregate_kernel(const AggArgs a)
+__global__ __launch_bounds__(kWave * kMaxWpb) __attribute__((amdgpu_waves_per_eu(K::MIN_WAVES))) void aggregate_kernel(const AggArgs a)
 {
     extern __shared__ uint4 stage_all[];        // LDS-staged variant: two stages of kStageSlots load instructions per wavefront
     const int lane = threadIdx.x & (kWave - 1);
