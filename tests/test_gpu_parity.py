@@ -331,7 +331,9 @@ def update_bound(a64, w64, k, bf16):
 
 @pytest.mark.parametrize("n_rows,d_in,d_out", [(1, 1, 1), (127, 16, 16), (129, 64, 64), (1000, 100, 256),
                                                (333, 602, 256), (4096, 256, 47), (77, 33, 300), (500, 5, 513), (300, 96, 512),
-                                               (257, 40, 256)])
+                                               (257, 40, 256),
+                                               # more row tiles than resident workgroups: each walks over several tiles
+                                               (70001, 100, 256), (66000, 36, 512)])
 @pytest.mark.parametrize("act", ["none", "relu"])
 def test_update_fp32(n_rows, d_in, d_out, act):
     rng = np.random.default_rng(n_rows + d_in)
