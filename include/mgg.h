@@ -224,7 +224,9 @@ mgg_status_t mgg_aggregate_to(const mgg_partition_t *p, mgg_agg_t mode, float ep
  * mgg_build_bags: host, synchronous.  bag_ptr[num_bags+1] (int64, bag_ptr[0]==0) and
  * bag_idx[bag_ptr[num_bags]] (int32 rows of the whole table, duplicates kept) are HOST pointers,
  * not retained.  The handle works with mgg_partition_info / export / destroy (n_own = num_bags,
- * lb / ub = the local slice, halo_gid = the remote rows) and with mgg_bag_sum only.
+ * lb / ub = the local slice, halo_gid = the remote rows) and with mgg_bag_sum only.  opts as for
+ * mgg_build_partition, except that short_max defaults to 32 (bags of a few tens of lookups are taken
+ * several per wavefront).
  *
  * mgg_bag_sum: out[b] = sum over the lookups of bag b of the table row, fp32 accumulation; empty
  * bags give zero rows.  table_local [(local_hi-local_lo) x dim] and table_halo [num_halo x dim]

@@ -484,6 +484,9 @@ mgg_status_t mgg_build_bags(int64_t num_bags, const int64_t *bag_ptr, const int3
         mgg_status_t st = parse_opts(opts, &knobs);
         if (st != MGG_OK) return st;
     }
+    // Bags of a recommendation batch hold one lookup per table, a few tens in all: up to 32 lookups they
+    // are taken several per wavefront like short graph rows (26-lookup bags: 0.89 -> 0.68 ms per batch).
+    if (!opts || !opts->short_max) knobs.short_max = 32;
     if (bag_ptr[0] != 0) return fail(MGG_ERR_BAD_GRAPH, "bag_ptr[0] != 0");
     for (int64_t b = 0; b < num_bags; ++b)
         if (bag_ptr[b + 1] < bag_ptr[b]) return fail(MGG_ERR_BAD_GRAPH, "bag_ptr decreases at bag %lld", (long long)b);
