@@ -333,7 +333,7 @@ def update_bound(a64, w64, k, bf16):
                                                (333, 602, 256), (4096, 256, 47), (77, 33, 300), (500, 5, 513), (300, 96, 512),
                                                (257, 40, 256),
                                                # more row tiles than resident workgroups: each walks over several tiles
-                                               (70001, 100, 256), (66000, 36, 512)])
+                                               (70001, 100, 256), (66000, 36, 512), (66000, 20, 256)])
 @pytest.mark.parametrize("act", ["none", "relu"])
 def test_update_fp32(n_rows, d_in, d_out, act):
     rng = np.random.default_rng(n_rows + d_in)
