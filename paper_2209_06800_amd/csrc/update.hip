@@ -4,7 +4,8 @@
 // Shape of the problem: A is tall (10^5..10^6 rows) and both d_in and d_out are small
 // (16..602).  A workgroup of four wavefronts covers a tile of (32*WM) rows x (NT*32*WN)
 // columns, WM*WN = 4; each wavefront owns 32 rows x NT*32 columns (NT <= 4, so that three
-// wavefronts fit a SIMD and the load phase of one overlaps the MFMA phase of another):
+// wavefronts fit a SIMD and the load phase of one overlaps the MFMA phase of another; NT = 8 with
+// two wavefronts per SIMD in the two-slab fp32 kernel, where a row of A is then read only once):
 //   - A goes straight from HBM into registers in the MFMA operand layout, the fragment of the
 //     next K slab being requested before the current slab is multiplied (no LDS round trip);
 //   - W is staged slab by slab in LDS and shared by the workgroup;
@@ -15,7 +16,8 @@
 //
 // launch_update picks per shape: the whole-line kernels of update_stream.hip where they apply
 // (HBM-bound shapes with whole K slabs), the kernels of this file otherwise -- weights resident in
-// LDS with a grid sized to the chip, or staged slab by slab (two slabs in LDS for the fp32 MFMA).
+// LDS with a grid sized to the chip, or staged slab by slab (two slabs in LDS for the fp32 MFMA,
+// filled by loads that go from global memory straight into LDS).
 // Row softmax runs as a second pass over the output.
 #include <hip/hip_runtime.h>
 
