@@ -57,12 +57,14 @@ def report_ratio(what, ratio):
 
 
 def check_aggregate(w_row_ptr, w_col, parts, part_id, bounds, x, mode, eps=0.0, build=None, ld_pad=0,
-                    misalign=0, rows=None, what="", report=None):
+                    misalign=0, rows=None, what="", report=None, options=None):
     """Run mgg_aggregate on one share and compare every (or the sampled) output row."""
     build = build or {}
     ref_part = oracle.build_partition(w_row_ptr, w_col, parts, part_id, bounds)
     lb, ub, hg = ref_part["lb"], ref_part["ub"], ref_part["halo_gid"]
     part = binding.mgg_build_partition(w_row_ptr, w_col, parts, part_id, bounds, **build)
+    for key, value in (options or {}).items():
+        part.set_option(key, value)
     x_local_np, x_halo_np = x[lb:ub], x[hg]
     dim = x.shape[1]
 
@@ -277,6 +279,22 @@ def test_column_slab_passes_give_the_same_answer(slab_bytes, dim, bf16):
     finally:
         binding.mgg_set_option("col_slab_bytes", 0)
         binding.mgg_set_option("lds_halo", 0)
+
+
+@pytest.mark.parametrize("slab_bytes", [1, 2048, 4096])
+@pytest.mark.parametrize("dim,bf16", [(300, False), (602, False), (1000, False), (1027, False), (1040, True), (2048, True), (2100, True)])
+def test_rows_wider_than_a_wavefront_without_narrow_slabs(slab_bytes, dim, bf16):
+    """With column slabs off (1) or wider than 1 KB a lane holds 2 to 4 chunks of a row (rows beyond 4 KB are
+    still walked 4 KB at a time): the kernel variants the automatic slab rule never picks."""
+    row_ptr, col, rng = small_rmat(seed=900 + dim)
+    n = row_ptr.size - 1
+    x = rng.standard_normal((n, dim)).astype(np.float32)
+    if bf16:
+        x = inputs.to_bf16_bits(x)
+    bounds = inputs.equal_node_bounds(n, 4)
+    for p, mode, build in ((0, "gcn", dict(xcd_min_deg=64)), (2, "gin", dict(dist=2))):
+        check_aggregate(row_ptr, col, 4, p, bounds, x, mode, eps=0.125, build=build, options={"col_slab_bytes": slab_bytes},
+                        what=f"wide rows, slab option {slab_bytes}, dim {dim} {mode}")
 
 
 @pytest.mark.parametrize("dim,bf16,mode", [(64, False, "gcn"), (100, False, "gin"), (602, False, "gcn"), (128, True, "gin")])
