@@ -40,11 +40,18 @@ OTHER_CONFIGS = (5, 2, 3)
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "measured_traffic.json")
 
 
+BUILD_KNOBS = {}          # --build-knob KEY=VALUE: knobs of mgg_build_partition for the timed run
+NON_DEFAULT_RUN = False   # set by --option / --build-knob: the record of measured traffic does not describe such a run
+
+
 def measured_traffic(workload: str, layer: int):
     """Bytes per aggregation launch that crossed from L2 to the memory fabric, from rocprofv3 --pmc runs
     (read and write requests destined for DRAM, 32-byte units, scaled by what the same counters read for
     a 1 GiB copy), as recorded in profiles/measured_traffic.json together with the commit the kernels
-    were at.  None when that workload and layer were not measured."""
+    were at.  None when that workload and layer were not measured, or when the run changes the library's
+    defaults (the record was taken with them)."""
+    if NON_DEFAULT_RUN:
+        return None
     try:
         with open(TRAFFIC_FILE) as f:
             rec = json.load(f)
@@ -488,7 +495,7 @@ def run(cfg: int, steps: int, warmup: int, verify: bool, cpu_budget_s: float = 2
         w.name += f"_share{part_id}"
     log(f"[bench] generated {w.name}: {inputs.graph_stats(w.row_ptr)} in {time.time() - t0:.1f}s")
     t0 = time.time()
-    part = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds)
+    part = binding.mgg_build_partition(w.row_ptr, w.col, w.parts, w.part_id, w.bounds, **BUILD_KNOBS)
     info = part.info
     halo_gid = part.export()["halo_gid"]
     nnz = int(info.nnz_local + info.nnz_remote)
@@ -741,6 +748,8 @@ def main():
                          "(known L2-miss bytes; reference for rocprofv3 --pmc runs) and exit")
     ap.add_argument("--option", action="append", default=[], metavar="KEY=VALUE",
                     help="a run-time switch of the library (mgg_set_option) for the whole run, e.g. col_slab_bytes=128")
+    ap.add_argument("--build-knob", action="append", default=[], metavar="KEY=VALUE",
+                    help="a knob of mgg_build_partition for the timed run, e.g. hot_phases=-2 or xcd_min_deg=128")
     ap.add_argument("--probe-gather", action="store_true",
                     help="time a bare gather kernel on tables from 1 MB to 2 GB (the ceilings of the gather path) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -750,10 +759,16 @@ def main():
         print("bench.py measures one GPU's share on one MI355X; multi-GPU runs are not part of this build "
               "(no collectives, no second GPU). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    global NON_DEFAULT_RUN
     for kv in args.option:
         from paper_2209_06800_amd import binding
         key, _, val = kv.partition("=")
         binding.mgg_set_option(key, int(val))
+        NON_DEFAULT_RUN = True
+    for kv in args.build_knob:
+        key, _, val = kv.partition("=")
+        BUILD_KNOBS[key] = int(val)
+        NON_DEFAULT_RUN = True
     if args.embedding_bags:
         print(json.dumps(run_embedding_bags()), flush=True)
         return
