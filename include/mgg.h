@@ -384,6 +384,7 @@ mgg_status_t mgg_tune_aggregate(int64_t num_nodes, const int64_t *row_ptr, const
  *                      bytes of an embedding row handled per pass over the work items
  *   "items_per_wave"   0 = automatic (default), or 1..64: work items a wavefront takes one after
  *                      the other, the next one's ids and descriptor requested while it gathers
+ *   "short_per_wave"   the same for the groups of short rows a wavefront takes
  *   "update_stream" 0/1 (process-wide only) the Update kernels added for streaming efficiency (whole-line
  *                      kernels, the one-kernel MLP, two W slabs in LDS) are used where they apply
  *                      (default 1; 0 = the plain register-resident and slab kernels everywhere)

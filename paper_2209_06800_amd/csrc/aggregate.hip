@@ -300,10 +300,9 @@ mgg_status_t launch_aggregate(const mgg_partition *p, mgg_agg_t mode, float eps,
     const int64_t n_groups = (a.n_items + wpb - 1) / wpb;
     const int64_t short_groups = (a.n_short + 64 / lpr - 1) / (64 / lpr);
     {
-        const int32_t opt = p->opt_items_per_wave;
-        auto pick = [&](int64_t units) { return static_cast<int32_t>(opt > 0 ? opt : std::min<int64_t>(2, std::max<int64_t>(1, units * n_slabs / 8192))); };
-        a.items_per_wave = pick(n_groups);
-        a.short_per_wave = pick((short_groups + wpb - 1) / wpb);
+        auto pick = [&](int32_t opt, int64_t units, int64_t most) { return static_cast<int32_t>(opt > 0 ? opt : std::min<int64_t>(most, std::max<int64_t>(1, units * n_slabs / 8192))); };
+        a.items_per_wave = pick(p->opt_items_per_wave, n_groups, 2);
+        a.short_per_wave = pick(p->opt_short_per_wave, (short_groups + wpb - 1) / wpb, 2);
     }
     a.n_item_blocks = static_cast<int32_t>((n_groups + static_cast<int64_t>(kXcd) * a.items_per_wave - 1) / (static_cast<int64_t>(kXcd) * a.items_per_wave) * kXcd);
     a.ps = p->ps;

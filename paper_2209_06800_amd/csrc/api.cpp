@@ -12,6 +12,7 @@ static std::atomic<int32_t> g_col_slab_bytes{0};
 static std::atomic<int32_t> g_split_phases{0};
 static std::atomic<int32_t> g_update_stream{1};
 static std::atomic<int32_t> g_items_per_wave{0};
+static std::atomic<int32_t> g_short_per_wave{0};
 int32_t option_lds_halo() { return g_lds_halo.load(); }
 int32_t option_col_slab_bytes() { return g_col_slab_bytes.load(); }
 int32_t option_split_phases() { return g_split_phases.load(); }
@@ -21,7 +22,7 @@ int32_t option_items_per_wave() { return g_items_per_wave.load(); }
 void take_default_options(mgg_partition *p)
 {
     p->opt_lds_halo = g_lds_halo.load(); p->opt_col_slab_bytes = g_col_slab_bytes.load();
-    p->opt_split_phases = g_split_phases.load(); p->opt_items_per_wave = g_items_per_wave.load();
+    p->opt_split_phases = g_split_phases.load(); p->opt_items_per_wave = g_items_per_wave.load(); p->opt_short_per_wave = g_short_per_wave.load();
 }
 
 mgg_status_t check_option(const char *key, int32_t value)
@@ -30,6 +31,10 @@ mgg_status_t check_option(const char *key, int32_t value)
     if (!std::strcmp(key, "col_slab_bytes")) {
         // 0: automatic, 1: off, otherwise a power of two between 64 and 4096
         if (value != 0 && value != 1 && (value < 64 || value > 4096 || (value & (value - 1)))) return fail(MGG_ERR_INVALID_ARG, "col_slab_bytes must be 0, 1 or a power of two in [64, 4096]");
+        return MGG_OK;
+    }
+    if (!std::strcmp(key, "short_per_wave")) {
+        if (value < 0 || value > 64) return fail(MGG_ERR_INVALID_ARG, "short_per_wave must be 0 (automatic) or 1..64");
         return MGG_OK;
     }
     if (!std::strcmp(key, "items_per_wave")) {
@@ -334,6 +339,7 @@ mgg_status_t mgg_set_option(const char *key, int32_t value)
     if (s != MGG_OK) return s;
     if (!std::strcmp(key, "col_slab_bytes")) g_col_slab_bytes = value;
     else if (!std::strcmp(key, "items_per_wave")) g_items_per_wave = value;
+    else if (!std::strcmp(key, "short_per_wave")) g_short_per_wave = value;
     else if (!std::strcmp(key, "lds_halo")) g_lds_halo = value;
     else if (!std::strcmp(key, "split_phases")) g_split_phases = value;
     else g_update_stream = value;
@@ -348,6 +354,7 @@ mgg_status_t mgg_get_option(const char *key, int32_t *value)
     if (!std::strcmp(key, "split_phases")) { *value = g_split_phases; return MGG_OK; }
     if (!std::strcmp(key, "update_stream")) { *value = g_update_stream; return MGG_OK; }
     if (!std::strcmp(key, "items_per_wave")) { *value = g_items_per_wave; return MGG_OK; }
+    if (!std::strcmp(key, "short_per_wave")) { *value = g_short_per_wave; return MGG_OK; }
     return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
 }
 
@@ -358,6 +365,7 @@ mgg_status_t mgg_partition_set_option(mgg_partition_t *p, const char *key, int32
     if (s != MGG_OK) return s;
     if (!std::strcmp(key, "col_slab_bytes")) p->opt_col_slab_bytes = value;
     else if (!std::strcmp(key, "items_per_wave")) p->opt_items_per_wave = value;
+    else if (!std::strcmp(key, "short_per_wave")) p->opt_short_per_wave = value;
     else if (!std::strcmp(key, "lds_halo")) p->opt_lds_halo = value;
     else if (!std::strcmp(key, "split_phases")) p->opt_split_phases = value;
     else return fail(MGG_ERR_INVALID_ARG, "'%s' is not a switch of the aggregation", key);
@@ -371,6 +379,7 @@ mgg_status_t mgg_partition_get_option(const mgg_partition_t *p, const char *key,
     if (!std::strcmp(key, "col_slab_bytes")) { *value = p->opt_col_slab_bytes; return MGG_OK; }
     if (!std::strcmp(key, "split_phases")) { *value = p->opt_split_phases; return MGG_OK; }
     if (!std::strcmp(key, "items_per_wave")) { *value = p->opt_items_per_wave; return MGG_OK; }
+    if (!std::strcmp(key, "short_per_wave")) { *value = p->opt_short_per_wave; return MGG_OK; }
     return fail(MGG_ERR_INVALID_ARG, "unknown option '%s'", key);
 }
 

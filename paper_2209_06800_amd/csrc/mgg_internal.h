@@ -79,7 +79,7 @@ struct mgg_partition {
     std::vector<mgg::SplitRow> split_rows;
     int64_t n_split_items = 0;
     // run-time switches of this partition's aggregations: the process-wide defaults at build time, then mgg_partition_set_option
-    int32_t opt_lds_halo = 0, opt_col_slab_bytes = 0, opt_split_phases = 0, opt_items_per_wave = 0;
+    int32_t opt_lds_halo = 0, opt_col_slab_bytes = 0, opt_split_phases = 0, opt_items_per_wave = 0, opt_short_per_wave = 0;
     int32_t reserved_dim = 0;         // widest aggregation the partition's own scratch buffer was sized for
     int64_t n_groups_local = 0, n_groups_remote = 0;
     mgg::DeviceArrays d;          // device copies; d.scratch is sized by mgg_partition_reserve (or at build)

@@ -332,7 +332,7 @@ def test_aggregation_switches_belong_to_a_partition():
     a.set_option("lds_halo", 1)
     a.set_option("split_phases", 1)
     assert a.get_option("lds_halo") == 1 and b.get_option("lds_halo") == 0 and binding.mgg_get_option("lds_halo") == 0
-    for key, bad in (("col_slab_bytes", 96), ("items_per_wave", 65), ("lds_halo", 2), ("update_stream", 1), ("nope", 0)):
+    for key, bad in (("col_slab_bytes", 96), ("items_per_wave", 65), ("short_per_wave", -1), ("lds_halo", 2), ("update_stream", 1), ("nope", 0)):
         assert _status(a.set_option, key, bad) == binding.ERR_INVALID_ARG
     with pytest.raises(MggError):
         a.get_option("update_stream")
